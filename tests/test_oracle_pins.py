@@ -1,0 +1,329 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here touches the GPU library.  Each test checks one routine of
+``oracle/solo_oracle.c`` against an independent statement of the same fact:
+values printed in the paper (tests/golden), closed forms, brute force over the
+level tables in binary64, numpy library routines, or a statistical law the
+paper proves.  The brute-force helpers below are deliberately written from the
+definitions (argmin over explicit level tables, full sort, ``np.power``) and
+not from the oracle's formulas.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from conftest import read_golden
+
+BITS = (2, 3, 4)
+
+
+def ulp32(x):
+    return np.spacing(np.float32(abs(x)))
+
+
+# ---------------------------------------------------------------- codebooks
+
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
+def test_signed_linear_level_set(so, bits):
+    """App. A: signed linear levels are {0, +-1/(2^(b-1)-1), ..., +-1}."""
+    L = 2 ** (bits - 1) - 1
+    want = sorted({k / L for k in range(-L, L + 1)})
+    got = [so.signed_level(c, bits) for c in range(2 * L + 1)]
+    assert got == want                      # exact rationals in binary64, monotone in the code
+    assert got[L] == 0.0 and got[0] == -1.0 and got[-1] == 1.0
+    for c in range(2 * L + 1):              # the dequantizer reproduces level * Delta
+        for scale in (1.0, 0.37, 3e-5):
+            x = float(so.dequant_m(c, scale, bits))
+            assert abs(x - got[c] * np.float32(scale)) <= 1.01 * ulp32(scale)
+    assert so.dequant_m(L, 123.456, bits) == 0.0
+
+
+def test_signed_linear_radii_match_paper(so):
+    """Fact A.1: radii 0.004 / 0.071 / 0.167 / 0.500 for 8/4/3/2 bits."""
+    for bits, radius in read_golden("signed_linear_radii.txt"):
+        bits, radius = int(bits), float(radius)
+        L = so.L_of(bits)
+        lv = [so.signed_level(c, bits) for c in range(2 * L + 1)]
+        r = min(b - a for a, b in zip(lv, lv[1:])) / 2
+        assert abs(r - radius) < 5.1e-4
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_m_quantizer_is_nearest_level(so, bits):
+    """Eq. 1: q = argmin_k |x/Delta - y_k| by brute force over the level table."""
+    rng = np.random.default_rng(10 + bits)
+    L = 2 ** (bits - 1) - 1
+    levels = np.array([k / L for k in range(-L, L + 1)])
+    for trial in range(40):
+        nb = int(rng.integers(1, 200))
+        x = (rng.standard_normal(nb) * 10.0 ** rng.uniform(-6, 2)).astype(np.float32)
+        codes, scale = so.quant_m_block(x, bits)
+        assert scale == np.max(np.abs(x))
+        z = x.astype(np.float64) / float(scale)
+        dist = np.abs(z[:, None] - levels[None, :])
+        brute = np.argmin(dist, axis=1)
+        srt = np.sort(dist, axis=1)
+        clear = (srt[:, 1] - srt[:, 0]) > 1e-5          # not an (almost) exact midpoint
+        assert np.array_equal(codes[clear], brute[clear])
+        assert np.all(np.abs(codes.astype(int) - brute) <= 1)
+        # round trip bound |x - Qdagger(Q(x))| <= r * Delta with r = 1/(2L)
+        back = np.array([so.dequant_m(int(c), scale, bits) for c in codes], np.float64)
+        assert np.all(np.abs(back - x) <= float(scale) / (2 * L) * (1 + 1e-6))
+        assert codes.max() <= 2 * L
+
+
+def test_m_quantizer_midpoints_round_to_even(so):
+    """Ties: x/Delta exactly between two levels goes to the even multiple."""
+    for bits in BITS:
+        L = 2 ** (bits - 1) - 1
+        # Delta = L makes x * (L/Delta) = x exactly
+        x = np.array([float(L)] + [k + 0.5 for k in range(-L, L)], np.float32)
+        codes, scale = so.quant_m_block(x, bits)
+        assert scale == L
+        want = [2 * L] + [L + int(np.rint(k + 0.5)) for k in range(-L, L)]
+        assert list(codes) == want
+
+
+@pytest.mark.parametrize("bits", BITS + (8,))
+def test_log_levels(so, bits):
+    """Sec. 3.2.2: y_k = alpha^k, k = 0..2^b-1, decreasing, y_0 = 1."""
+    K = 2 ** bits - 1
+    for alpha in (0.9999, 0.93, 0.5, 0.12, 2.0 ** (-64 / K)):
+        if alpha ** K < 1e-30:
+            continue                        # the low levels would underflow binary32
+        a32 = np.float32(alpha)
+        lv = np.array([so.log_level(a32, k, bits) for k in range(K + 1)], np.float64)
+        ref = np.power(float(a32), np.arange(K + 1))
+        assert lv[0] == 1.0 and lv[1] == float(a32)
+        assert np.all(np.diff(lv) < 0)
+        # every rounded product adds at most half an ulp and squaring doubles what is there:
+        # alpha^k carries at most about k ulps
+        assert np.all(np.abs(lv / ref - 1) <= (np.arange(K + 1) + bits) * 2.0 ** -24)
+        assert so.dequant_v(0, 0.731, a32, bits) == np.float32(0.731)
+    assert so.log_level(np.float32(1.0), K, bits) == 1.0
+
+
+@pytest.mark.parametrize("bits", BITS + (8, 16))
+def test_root_is_largest_base_under_rho(so, bits):
+    """alpha = (x_p/Delta)^(1/(2^b-1)): the last level equals x_p/Delta up to rounding,
+    and alpha is the largest binary32 with last level <= rho."""
+    K = 2 ** bits - 1
+    rng = np.random.default_rng(bits)
+    rhos = np.concatenate([2.0 ** rng.uniform(-64, 0, 300), [2.0 ** -64, 0.5, 1 - 2.0 ** -24,
+                                                             0.999999, 1e-3]]).astype(np.float32)
+    for rho in rhos:
+        a = so.root(rho, bits)
+        assert 0 < a < 1
+        last = so.log_level(a, K, bits)
+        assert last <= rho
+        up = np.nextafter(a, np.float32(2.0))
+        assert up == 1.0 or so.log_level(up, K, bits) > rho
+        exact = float(rho) ** (1.0 / K)
+        assert abs(float(a) / exact - 1) <= 2.0 ** -22
+    assert so.root(np.float32(1.0), bits) == 1.0
+
+
+def test_rank_of_the_quantile(so):
+    assert so.rank(0.1, 128) == 13 and so.rank(0.1, 64) == 7
+    assert so.rank(0.0, 128) == 1 and so.rank(0.1, 1) == 1 and so.rank(0.1, 10) == 1
+    assert so.rank(0.25, 128) == 32 and so.rank(0.3, 128) == 39 and so.rank(0.05, 128) == 7
+    for nb in range(1, 300):
+        for num in range(0, 16):               # dyadic p: p*nb is exact in binary32
+            p = num / 16.0
+            assert so.rank(p, nb) == min(nb, max(1, math.ceil(p * nb)))
+
+
+def test_order_statistic_is_sorted_rank(so):
+    rng = np.random.default_rng(5)
+    for trial in range(50):
+        nb = int(rng.integers(1, 300))
+        x = rng.choice(rng.standard_normal(40).astype(np.float32) ** 2, nb)   # many ties
+        r = int(rng.integers(1, nb + 1))
+        assert so.order_statistic(x, r) == np.sort(x)[r - 1]
+
+
+# ------------------------------------------------------------ v quantizer
+
+def brute_v_codes(x, scale, alpha, xi, bits):
+    """Clip(round(log_alpha(x/Delta) + xi); 0, K) by explicit enumeration in binary64."""
+    K = 2 ** bits - 1
+    with np.errstate(divide="ignore"):
+        t = np.log(x.astype(np.float64) / float(scale)) / math.log(float(alpha)) + xi
+    ks = np.arange(K + 1)
+    dist = np.abs(t[:, None] - ks[None, :])
+    dist[np.isnan(dist)] = 0
+    codes = np.argmin(dist, axis=1)
+    codes[x == 0] = K
+    srt = np.sort(dist, axis=1)
+    with np.errstate(invalid="ignore"):
+        margin = (srt[:, 1] - srt[:, 0]) / 2        # distance of t to the boundary k+0.5
+    margin[x == 0] = np.inf
+    return codes, margin
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("stochastic", (0, 1))
+def test_v_quantizer_against_brute_force(so, bits, stochastic):
+    rng = np.random.default_rng(100 + bits)
+    K = 2 ** bits - 1
+    worst = 0
+    for trial in range(60):
+        nb = int(rng.choice([128, 64, 37, 128, 5]))
+        g = rng.standard_normal(nb) * 10.0 ** rng.uniform(-6, 0)
+        x = (g * g).astype(np.float32)
+        if trial % 7 == 0:
+            x[rng.random(nb) < 0.3] = 0.0                      # sparse rows: zero entries
+        p = float(rng.choice([0.1, 0.05, 0.3, 0.0]))
+        i0 = int(rng.integers(0, 1 << 40)) * 8
+        step = int(rng.integers(1, 1000))
+        codes, scale, alpha, margin = so.quant_v_block(x, bits, p, stochastic, 42, step, i0,
+                                                      want_margin=True)
+        assert scale == x.max()
+        xp = np.sort(x)[so.rank(p, nb) - 1]
+        rho = max(float(np.float32(xp) / np.float32(scale)), 2.0 ** -64)
+        assert abs(float(alpha) / rho ** (1.0 / K) - 1) <= 2.0 ** -22
+        xi = so.xi_array(42, step, i0, nb).astype(np.float64) if stochastic else np.zeros(nb)
+        brute, bmargin = brute_v_codes(x, scale, alpha, xi, bits)
+        clear = bmargin > 1e-5
+        assert np.array_equal(codes[clear], brute[clear])
+        assert np.all(np.abs(codes.astype(int) - brute) <= 1)
+        worst = max(worst, int(np.sum(~clear)))
+        fin = np.isfinite(bmargin) & (bmargin < 0.4)
+        assert np.allclose(margin[fin], bmargin[fin], atol=1e-9, rtol=1e-6)   # the margin helper
+        assert codes[np.argmax(x)] == 0                        # the block maximum decodes to Delta
+        assert np.all(codes[x == 0] == K)
+    assert worst <= 2
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_v_round_trip_bounds(so, bits):
+    """Nearest rounding in the log domain: inside [x_p, Delta] the decoded value is within a
+    factor alpha^(+-1/2); below x_p everything takes the smallest level; with xi the factor
+    is alpha^(+-1)."""
+    rng = np.random.default_rng(200 + bits)
+    K = 2 ** bits - 1
+    for stochastic, span in ((0, 0.5), (1, 1.0)):
+        for trial in range(30):
+            g = rng.standard_normal(128) * 1e-3
+            x = (g * g).astype(np.float32)
+            codes, scale, alpha = so.quant_v_block(x, bits, 0.1, stochastic, 7, trial + 1, 0)
+            back = np.array([so.dequant_v(int(c), scale, alpha, bits) for c in codes], np.float64)
+            xp = np.sort(x)[12]
+            inside = x >= xp
+            ratio = back[inside] / x[inside]
+            lo, hi = float(alpha) ** span, float(alpha) ** -span
+            assert np.all(ratio >= lo * (1 - 1e-5)) and np.all(ratio <= hi * (1 + 1e-5))
+            if not stochastic:
+                assert np.all(codes[x < xp * float(alpha) ** 0.5 * (1 - 1e-5)] == K)
+            assert back[np.argmax(x)] == float(scale)
+            # the smallest level reproduces x_p up to the rounding of the root
+            assert abs(so.dequant_v(K, scale, alpha, bits) / xp - 1) < 1e-5
+
+
+def test_log_domain_rounding_gives_exact_decay(so):
+    """Prop. 3.4: with alpha = beta^c and zero signals, a state alpha^k drops one level with
+    probability exactly 1/c per update and never moves otherwise; s levels take c*s updates
+    on average.  True for rounding in the log domain only: nearest rounding in the linear
+    domain with the same xi would drop with probability 1/c + 1/2 - log_alpha((1+alpha)/2)."""
+    beta, c, bits = 0.9, 5, 3
+    alpha = np.float32(beta ** c)
+    n = 200000
+    xi = so.xi_array(3, 17, 0, n)
+    for k in (0, 2, 5):
+        state = float(so.log_level(alpha, k, bits))
+        x = np.float32(beta * state)                      # EMA with z = 0, Delta fixed at 1
+        codes = np.array([so.quant_v_elem(x, 1.0, alpha, float(e), bits) for e in xi[:n]])
+        assert set(np.unique(codes)) <= {k, k + 1}
+        frac = np.mean(codes == k + 1)
+        sigma = math.sqrt((1 / c) * (1 - 1 / c) / n)
+        assert abs(frac - 1 / c) < 5 * sigma
+        wrong = 1 / c + 0.5 - math.log((1 + float(alpha)) / 2) / math.log(float(alpha))
+        assert abs(frac - wrong) > 20 * sigma
+    # expected number of updates to fall s = 3 levels from level 1
+    rng_walkers, s = 4000, 3
+    code = np.ones(rng_walkers, int)
+    steps = np.zeros(rng_walkers, int)
+    t = 0
+    active = code < 1 + s
+    while active.any():
+        t += 1
+        e = so.xi_array(11, t, 0, rng_walkers)
+        for w in np.nonzero(active)[0]:
+            x = np.float32(beta * float(so.log_level(alpha, int(code[w]), bits)))
+            code[w] = so.quant_v_elem(x, 1.0, alpha, float(e[w]), bits)
+            steps[w] = t
+        active = code < 1 + s
+        assert t < 400
+    assert abs(steps.mean() - c * s) < 5 * math.sqrt(s * (1 - 1 / c) * c * c / rng_walkers)
+
+
+# ---------------------------------------------------------------- xi stream
+
+def test_xi_stream_is_uniform_and_uncorrelated(so):
+    n = 1 << 18
+    a = so.xi_array(42, 1, 0, n).astype(np.float64)
+    b = so.xi_array(42, 2, 0, n).astype(np.float64)
+    c = so.xi_array(43, 1, 0, n).astype(np.float64)
+    far = so.xi_array(42, 1, (1 << 40), 4096).astype(np.float64)
+    for x in (a, b, c):
+        assert x.min() > -0.5 and x.max() < 0.5                       # open interval
+        assert abs(x.mean()) < 5 * math.sqrt(1 / 12 / n)
+        assert abs(x.var() - 1 / 12) < 5 * (1 / 12) * math.sqrt(0.8 / n)
+        hist = np.histogram(x, 256, (-0.5, 0.5))[0]
+        chi2 = np.sum((hist - n / 256) ** 2 / (n / 256))
+        assert chi2 < 255 + 6 * math.sqrt(2 * 255)
+    def corr(x, y):
+        return abs(np.mean(x * y)) * 12
+    lim = 5 / math.sqrt(n)
+    for lag in (1, 2, 3, 7, 8, 9, 64, 128):
+        assert corr(a[:-lag], a[lag:]) < lim                          # neighbours, across groups
+    assert corr(a, b) < lim and corr(a, c) < lim                      # across steps and seeds
+    assert abs(far.mean()) < 5 * math.sqrt(1 / 12 / 4096)
+    assert not np.array_equal(far, a[:4096])
+    # (u + 1/2)/2^24 - 1/2 exactly: xi * 2^25 is an odd integer
+    k = a * 2.0 ** 25
+    assert np.all(k == np.rint(k)) and np.all(np.mod(k, 2) == 1)
+    # pure function of (seed, step, index)
+    assert so.xi(so.xi_keys(42, 1), 12345) == np.float32(a[12345])
+
+
+# ------------------------------------------------------------------ packing
+
+def test_pack_layout_literals(so):
+    assert (so.codes_per_word(2), so.codes_per_word(3), so.codes_per_word(4)) == (16, 10, 8)
+    assert list(so.pack(np.array([1, 2, 3], np.uint16), 2)) == [0x39]
+    assert list(so.pack(np.array([1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 5], np.uint16), 3)) == \
+        [0b010_001_000_111_110_101_100_011_010_001, 0b101]
+    assert list(so.pack(np.array([1, 2, 3, 15, 0, 0, 0, 8, 9], np.uint16), 4)) == [0x8000F321, 0x9]
+    assert so.code_words(128, 3) == 13 and so.code_words(2560, 3) == 256
+    assert so.code_words(0, 2) == 0 and so.code_words(17, 2) == 2
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_pack_unpack_bijection(so, bits):
+    rng = np.random.default_rng(bits)
+    for n in (1, 9, 10, 11, 16, 127, 128, 641, 2560, 5003):
+        codes = rng.integers(0, 2 ** bits, n).astype(np.uint16)
+        words = so.pack(codes, bits)
+        assert words.size == -(-n // (32 // bits))
+        assert np.array_equal(so.unpack(words, n, bits), codes)
+        if bits == 3:
+            assert np.all(words >> 30 == 0)                       # two pad bits stay zero
+        used = n * bits if bits != 3 else None
+        if used is not None and n % (32 // bits):
+            assert words[-1] >> (bits * (n % (32 // bits))) == 0  # tail of the last word is zero
+
+
+def test_state_init_is_the_zero_state(so):
+    lit = {2: 0x55555555, 3: 0x1B6DB6DB, 4: 0x77777777}           # code L in every field
+    for bm in BITS:
+        for bv in BITS:
+            cfg = so.make_config(bits_m=bm, bits_v=bv, block_size=128)
+            st = so.State(1280, cfg)
+            assert np.all(st.m_words == lit[bm]) and np.all(st.v_words == 0)
+            assert np.all(st.m_scale == 0) and np.all(st.v_scale == 0) and np.all(st.v_base == 1)
+            assert st.m_scale.size == 10
+    st = so.State(130, so.make_config(bits_m=2, bits_v=3, block_size=64))
+    assert st.m_scale.size == 3 and st.m_words.size == 9 and st.v_words.size == 13
+    assert st.m_words[-1] == 0x5                                  # two codes, rest zero
