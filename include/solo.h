@@ -1,0 +1,128 @@
+/*
+ * libsolo — the SOLO low-bit AdamW optimizer step for AMD MI355X (gfx950).
+ *
+ * One call performs, in a single pass over HBM, the whole quantized-state
+ * update of "Pushing the Limits of Low-Bit Optimizers: A Focus on EMA
+ * Dynamics" (SOLO) for one flat buffer of parameters:
+ *
+ *   dequantize both moments  ->  EMA update  ->  AdamW parameter update
+ *   ->  per-block scale / quantile / log base  ->  re-quantize  ->  re-pack
+ *
+ *   1st moment  m : b_m-bit signed linear codes            (App. A, Eq. 1)
+ *   2nd moment  v : b_v-bit unsigned logarithmic codes, levels alpha^k,
+ *                   log-domain stochastic rounding, per-block base alpha
+ *                   from the p-quantile                     (Sec. 3.2.2)
+ *   block-wise quantization, one scale per block            (Sec. 3.4)
+ *
+ * Conventions for every entry point
+ *   - Pointers named param / grad / *_codes / *_scale / v_base are DEVICE
+ *     pointers; `cfg` is a HOST pointer, read during the call only.
+ *   - All buffers are owned by the caller.  The library never allocates,
+ *     frees or keeps a pointer, and never synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     the call returns at once.
+ *   - Return value: SOLO_OK (0) or a negative error code; nothing is enqueued
+ *     when an error is returned.  n == 0 is a successful no-op.
+ *
+ * State layout for n elements, block size B, nb = ceil(n / B) blocks
+ *   m_codes  uint32[solo_code_words(n, bits_m)]   element i lives in word
+ *   v_codes  uint32[solo_code_words(n, bits_v)]   i / c at bit bits*(i mod c),
+ *            c = 16 (2-bit), 10 (3-bit, two pad bits), 8 (4-bit); unused bits 0
+ *   m_scale  float[nb]   Delta_m = max |m| of the block
+ *   v_scale  float[nb]   Delta_v = max v of the block
+ *   v_base   float[nb]   alpha of the block, in (0, 1]
+ *   A 1st-moment code c in [0, 2L], L = 2^(bits_m-1)-1, stands for the level
+ *   (c - L) / L; a 2nd-moment code q in [0, 2^bits_v - 1] for alpha^q.
+ *   param, grad and the code buffers must be 16-byte aligned, the scale
+ *   buffers 4-byte aligned.
+ */
+#ifndef SOLO_H
+#define SOLO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SOLO_OK = 0,
+    SOLO_E_INVALID = -1,      /* null/misaligned pointer, value out of range   */
+    SOLO_E_UNSUPPORTED = -2,  /* legal value this build has no kernel for      */
+    SOLO_E_HIP = -3           /* the HIP runtime refused the launch            */
+};
+
+enum { SOLO_GRAD_FP32 = 0, SOLO_GRAD_BF16 = 1 };
+
+/* flags */
+#define SOLO_FLAG_STOCHASTIC 1u   /* xi ~ U(-0.5, 0.5); clear = xi = 0 */
+
+typedef struct solo_config {
+    uint32_t bits_m;       /* 2, 3 or 4: signed linear codes (App. A)                  */
+    uint32_t bits_v;       /* 2, 3 or 4: logarithmic codes (Sec. 3.2.2)                */
+    uint32_t block_size;   /* 64 or 128 elements per block (Sec. 3.4 uses 128)         */
+    uint32_t grad_dtype;   /* SOLO_GRAD_FP32 or SOLO_GRAD_BF16                         */
+    float lr;              /* learning rate                                            */
+    float beta1;           /* momentum of the signed EMA, in [0,1); use the precision- */
+                           /* specific value of Sec. 3.3 (solo_beta1_default)          */
+    float beta2;           /* momentum of the unsigned EMA, in [0,1)                   */
+    float eps;             /* added to the bias-corrected root, >= 0                   */
+    float weight_decay;    /* decoupled decay                                          */
+    float quantile_p;      /* p of the quantile that sets alpha, in [0,1); paper: 0.1  */
+    uint32_t flags;        /* SOLO_FLAG_*                                              */
+    uint32_t reserved;     /* must be 0                                                */
+    uint64_t seed;         /* key of the xi stream                                     */
+    uint64_t index_offset; /* global index of element 0 of this buffer; multiple of 8. */
+                           /* xi is a function of (seed, step, index_offset + i), so a */
+                           /* shard of a larger buffer reproduces the unsharded result */
+} solo_config;
+
+/* Number of uint32 words that hold n codes of the given width (2, 3 or 4);
+ * 0 for an unsupported width. */
+size_t solo_code_words(uint64_t n, uint32_t bits);
+
+/* ceil(n / block_size); 0 if block_size is 0. */
+size_t solo_num_blocks(uint64_t n, uint32_t block_size);
+
+/* Bytes of optimizer state for n elements: both code buffers plus three
+ * floats per block (Sec. 4.2: the scale costs 32/B bits per element and the
+ * buffered log base doubles that). 0 if cfg is invalid. */
+size_t solo_state_bytes(uint64_t n, const solo_config *cfg);
+
+/* Default momentum of the signed EMA for a code width (Sec. 3.4): 4-bit 0.8
+ * (fine-tuning) / 0.3 (from scratch), 2-bit 0.5 / 0.1; 3-bit, which the paper
+ * does not list, takes 0.6 / 0.2 by the same rule.  Other widths: 0.9. */
+float solo_beta1_default(uint32_t bits_m, int from_scratch);
+
+/* Largest beta' with beta'/(1-beta') * r_median(b') <= beta/(1-beta) * r_median(b)
+ * (Sec. 3.3, Eq. "beta-prime"), given the two median radii. */
+float solo_beta1_bound(float beta, float r_median_b, float r_median_bprime);
+
+/* Write the zero state: every 1st-moment code = L (level 0), every
+ * 2nd-moment code = 0, Delta_m = Delta_v = 0, alpha = 1. */
+int solo_state_init(uint32_t *m_codes, float *m_scale,
+                    uint32_t *v_codes, float *v_scale, float *v_base,
+                    uint64_t n, const solo_config *cfg, void *stream);
+
+/* One optimizer step (Sec. 3.1 Eqs. 2-4 for both moments, Sec. 3.2.2 for the
+ * 2nd-moment quantizer, Sec. 3.4 for blocks), in place:
+ *   param   float[n], read and written
+ *   grad    float[n] or bf16[n] per cfg->grad_dtype, read only
+ *   states  as laid out above, read and written
+ *   step    1-based count of this update (bias correction and xi stream)
+ * Gradients must be finite.  A block whose new maximum is below 2^-100 is
+ * stored as a zero block. */
+int solo_adamw_step(float *param, const void *grad,
+                    uint32_t *m_codes, float *m_scale,
+                    uint32_t *v_codes, float *v_scale, float *v_base,
+                    uint64_t n, uint64_t step,
+                    const solo_config *cfg, void *stream);
+
+/* Static, human-readable text for a return code. */
+const char *solo_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOLO_H */

@@ -1,0 +1,195 @@
+// Host side of libsolo: argument checks, per-step scalars, kernel dispatch.
+// See include/solo.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/solo.h"
+#include "solo_step.h"
+
+namespace solo {
+
+template <int BM>
+hipError_t launch_step(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
+                       bool has_tail, hipStream_t stream);
+template <> hipError_t launch_step<2>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<3>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<4>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+
+static bool bits_ok(uint32_t b) { return b >= 2 && b <= 4; }
+
+static bool config_ok(const solo_config *c)
+{
+    if (!c) return false;
+    if (!bits_ok(c->bits_m) || !bits_ok(c->bits_v)) return false;
+    if (c->block_size != 64 && c->block_size != 128) return false;
+    if (c->grad_dtype != SOLO_GRAD_FP32 && c->grad_dtype != SOLO_GRAD_BF16) return false;
+    if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f) || !(c->beta2 >= 0.0f && c->beta2 < 1.0f)) return false;
+    if (!(c->quantile_p >= 0.0f && c->quantile_p < 1.0f)) return false;
+    if (!(c->eps >= 0.0f) || !isfinite(c->eps)) return false;
+    if (!isfinite(c->lr) || !isfinite(c->weight_decay)) return false;
+    if ((c->flags & ~SOLO_FLAG_STOCHASTIC) != 0 || c->reserved != 0) return false;
+    if (c->index_offset % 8 != 0) return false;
+    return true;
+}
+
+static bool aligned(const void *p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// One code word with the code of level 0 in each of `fields` slots.
+__host__ __device__ static uint32_t zero_level_word(uint32_t bits, uint32_t fields)
+{
+    const uint32_t L = (1u << (bits - 1)) - 1u;
+    uint32_t w = 0;
+    for (uint32_t k = 0; k < fields; ++k) w |= L << (bits * k);
+    return w;
+}
+
+__global__ void init_kernel(uint32_t *m_words, float *m_scale, uint32_t *v_words, float *v_scale,
+                            float *v_base, uint64_t m_total, uint64_t v_total, uint64_t nblk,
+                            uint32_t full_word, uint32_t last_word)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < m_total; i += stride)
+        m_words[i] = (i + 1 == m_total) ? last_word : full_word;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < v_total; i += stride)
+        v_words[i] = 0u;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nblk; i += stride) {
+        m_scale[i] = 0.0f; v_scale[i] = 0.0f; v_base[i] = 1.0f;
+    }
+}
+
+// 64-bit finalizer used to derive the per-step keys of the xi stream.
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+}  // namespace solo
+
+extern "C" {
+
+size_t solo_code_words(uint64_t n, uint32_t bits)
+{
+    if (!solo::bits_ok(bits)) return 0;
+    const uint64_t c = 32u / bits;
+    return (size_t)((n + c - 1) / c);
+}
+
+size_t solo_num_blocks(uint64_t n, uint32_t block_size)
+{
+    return block_size ? (size_t)((n + block_size - 1) / block_size) : 0;
+}
+
+size_t solo_state_bytes(uint64_t n, const solo_config *cfg)
+{
+    if (!solo::config_ok(cfg)) return 0;
+    return 4 * (solo_code_words(n, cfg->bits_m) + solo_code_words(n, cfg->bits_v)) +
+           12 * solo_num_blocks(n, cfg->block_size);
+}
+
+float solo_beta1_default(uint32_t bits_m, int from_scratch)
+{
+    switch (bits_m) {
+    case 4: return from_scratch ? 0.3f : 0.8f;
+    case 3: return from_scratch ? 0.2f : 0.6f;
+    case 2: return from_scratch ? 0.1f : 0.5f;
+    default: return 0.9f;
+    }
+}
+
+float solo_beta1_bound(float beta, float r_median_b, float r_median_bprime)
+{
+    if (!(beta >= 0.0f && beta < 1.0f) || !(r_median_b > 0.0f) || !(r_median_bprime > 0.0f)) return 0.0f;
+    const double x = (double)beta / (1.0 - (double)beta) * (double)r_median_b / (double)r_median_bprime;
+    return (float)(x / (1.0 + x));
+}
+
+const char *solo_strerror(int code)
+{
+    switch (code) {
+    case SOLO_OK: return "success";
+    case SOLO_E_INVALID: return "invalid argument (null or misaligned pointer, or a value out of range)";
+    case SOLO_E_UNSUPPORTED: return "configuration not supported by this build";
+    case SOLO_E_HIP: return "the HIP runtime reported an error at launch";
+    default: return "unknown error code";
+    }
+}
+
+int solo_state_init(uint32_t *m_codes, float *m_scale, uint32_t *v_codes, float *v_scale,
+                    float *v_base, uint64_t n, const solo_config *cfg, void *stream)
+{
+    if (!solo::config_ok(cfg)) return SOLO_E_INVALID;
+    if (n == 0) return SOLO_OK;
+    if (!solo::aligned(m_codes, 16) || !solo::aligned(v_codes, 16) || !solo::aligned(m_scale, 4) ||
+        !solo::aligned(v_scale, 4) || !solo::aligned(v_base, 4))
+        return SOLO_E_INVALID;
+    const uint32_t cm = 32u / cfg->bits_m;
+    const uint64_t m_total = solo_code_words(n, cfg->bits_m), v_total = solo_code_words(n, cfg->bits_v);
+    const uint64_t nblk = solo_num_blocks(n, cfg->block_size);
+    const uint32_t rem = (uint32_t)(n % cm);
+    const uint32_t full = solo::zero_level_word(cfg->bits_m, cm);
+    const uint32_t last = solo::zero_level_word(cfg->bits_m, rem ? rem : cm);
+    uint64_t blocks = (m_total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(solo::init_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream,
+                       m_codes, m_scale, v_codes, v_scale, v_base, m_total, v_total, nblk, full, last);
+    return hipGetLastError() == hipSuccess ? SOLO_OK : SOLO_E_HIP;
+}
+
+int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_scale,
+                    uint32_t *v_codes, float *v_scale, float *v_base, uint64_t n, uint64_t step,
+                    const solo_config *cfg, void *stream)
+{
+    if (!solo::config_ok(cfg) || step == 0) return SOLO_E_INVALID;
+    if (n == 0) return SOLO_OK;
+    if (!solo::aligned(param, 16) || !solo::aligned(grad, 16) || !solo::aligned(m_codes, 16) ||
+        !solo::aligned(v_codes, 16) || !solo::aligned(m_scale, 4) || !solo::aligned(v_scale, 4) ||
+        !solo::aligned(v_base, 4))
+        return SOLO_E_INVALID;
+    if (n > (1ull << 40)) return SOLO_E_UNSUPPORTED;
+
+    solo::StepArgs a;
+    a.param = param; a.grad = grad;
+    a.m_words = m_codes; a.m_scale = m_scale;
+    a.v_words = v_codes; a.v_scale = v_scale; a.v_base = v_base;
+    a.n = n;
+    a.n_tiles_full = n / solo::kTile;
+    a.index_offset = cfg->index_offset;
+    a.beta1 = cfg->beta1; a.omb1 = 1.0f - cfg->beta1;
+    a.beta2 = cfg->beta2; a.omb2 = 1.0f - cfg->beta2;
+    // bias corrections and the folded step scalars, in binary64 on the host
+    const double bc1 = 1.0 - pow((double)cfg->beta1, (double)step);
+    const double bc2 = 1.0 - pow((double)cfg->beta2, (double)step);
+    a.decay = (float)(1.0 - (double)cfg->lr * (double)cfg->weight_decay);
+    a.step_size = (float)((double)cfg->lr / bc1);
+    a.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+    a.eps = cfg->eps;
+    a.quantile_p = cfg->quantile_p;
+    // r = max(1, ceil(p * B)) with the product in binary32
+    float x = ceilf(cfg->quantile_p * (float)cfg->block_size);
+    a.rank_full = x < 1.0f ? 1u : (uint32_t)x;
+    if (a.rank_full > cfg->block_size) a.rank_full = cfg->block_size;
+    // keys of this step's xi stream
+    const uint64_t gamma = 0x9E3779B97F4A7C15ull;
+    const uint64_t z = cfg->seed + gamma * step;
+    const uint64_t ka = solo::mix64(z + gamma), kb = solo::mix64(z + 2 * gamma);
+    a.key0 = (uint32_t)ka; a.key1 = (uint32_t)(ka >> 32); a.key2 = (uint32_t)kb;
+    const bool stochastic = (cfg->flags & SOLO_FLAG_STOCHASTIC) != 0;
+    a.xi_scale = stochastic ? 0x1p-24f : 0.0f;
+    a.xi_offset = stochastic ? (0x1p-25f - 0.5f) : 0.0f;
+
+    const bool has_tail = (n % solo::kTile) != 0;
+    const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;
+    hipError_t e;
+    switch (cfg->bits_m) {
+    case 2: e = solo::launch_step<2>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, (hipStream_t)stream); break;
+    case 3: e = solo::launch_step<3>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, (hipStream_t)stream); break;
+    case 4: e = solo::launch_step<4>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, (hipStream_t)stream); break;
+    default: return SOLO_E_UNSUPPORTED;
+    }
+    return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;
+}
+
+}  // extern "C"

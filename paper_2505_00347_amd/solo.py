@@ -1,0 +1,131 @@
+"""Thin Python binding of libsolo (see include/solo.h): argument marshalling only.
+
+Every function has the name and meaning of the C entry point it calls; all of the
+optimizer step runs in the HIP kernels of the library.  Tensors are torch tensors
+on an AMD GPU (torch is used for device memory and streams only); a tensor is
+passed as its device pointer, the stream as the current torch stream's handle.
+The module fails loudly when the library has not been built: there is no
+fallback path.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libsolo.so")
+
+SOLO_OK, SOLO_E_INVALID, SOLO_E_UNSUPPORTED, SOLO_E_HIP = 0, -1, -2, -3
+SOLO_GRAD_FP32, SOLO_GRAD_BF16 = 0, 1
+SOLO_FLAG_STOCHASTIC = 1
+
+
+class solo_config(C.Structure):
+    _fields_ = [("bits_m", C.c_uint32), ("bits_v", C.c_uint32), ("block_size", C.c_uint32),
+                ("grad_dtype", C.c_uint32),
+                ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("quantile_p", C.c_float),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32),
+                ("seed", C.c_uint64), ("index_offset", C.c_uint64)]
+
+
+def make_config(bits_m=4, bits_v=4, block_size=128, grad_dtype=SOLO_GRAD_FP32, lr=1e-3,
+                beta1=None, beta2=0.999, eps=1e-8, weight_decay=0.01, quantile_p=0.1,
+                flags=SOLO_FLAG_STOCHASTIC, seed=42, index_offset=0):
+    if beta1 is None:
+        beta1 = solo_beta1_default(bits_m, 0)
+    return solo_config(bits_m, bits_v, block_size, grad_dtype, lr, beta1, beta2, eps,
+                       weight_decay, quantile_p, flags, 0, seed, index_offset)
+
+
+class SoloError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"libsolo error {code}: {solo_strerror(code)}")
+
+
+_lib = None
+
+
+def lib():
+    """Load libsolo.so (built by ``python -m paper_2505_00347_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_2505_00347_amd.build` (needs hipcc)")
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64, cfgp = C.c_void_p, C.c_uint32, C.c_uint64, C.POINTER(solo_config)
+        L.solo_code_words.restype = C.c_size_t; L.solo_code_words.argtypes = [u64, u32]
+        L.solo_num_blocks.restype = C.c_size_t; L.solo_num_blocks.argtypes = [u64, u32]
+        L.solo_state_bytes.restype = C.c_size_t; L.solo_state_bytes.argtypes = [u64, cfgp]
+        L.solo_beta1_default.restype = C.c_float; L.solo_beta1_default.argtypes = [u32, C.c_int]
+        L.solo_beta1_bound.restype = C.c_float
+        L.solo_beta1_bound.argtypes = [C.c_float, C.c_float, C.c_float]
+        L.solo_strerror.restype = C.c_char_p; L.solo_strerror.argtypes = [C.c_int]
+        L.solo_state_init.restype = C.c_int
+        L.solo_state_init.argtypes = [vp, vp, vp, vp, vp, u64, cfgp, vp]
+        L.solo_adamw_step.restype = C.c_int
+        L.solo_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, u64, cfgp, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or a raw integer address)."""
+    return t if isinstance(t, int) else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def solo_code_words(n, bits): return lib().solo_code_words(n, bits)
+def solo_num_blocks(n, block_size): return lib().solo_num_blocks(n, block_size)
+def solo_state_bytes(n, cfg): return lib().solo_state_bytes(n, C.byref(cfg))
+def solo_beta1_default(bits_m, from_scratch=0): return lib().solo_beta1_default(bits_m, from_scratch)
+def solo_beta1_bound(beta, r_median_b, r_median_bprime): return lib().solo_beta1_bound(beta, r_median_b, r_median_bprime)
+def solo_strerror(code): return lib().solo_strerror(code).decode()
+
+
+def solo_state_init(m_codes, m_scale, v_codes, v_scale, v_base, n, cfg, stream=None, check=True):
+    rc = lib().solo_state_init(_ptr(m_codes), _ptr(m_scale), _ptr(v_codes), _ptr(v_scale),
+                               _ptr(v_base), n, C.byref(cfg), _stream(stream) if n else None)
+    if check and rc != SOLO_OK:
+        raise SoloError(rc)
+    return rc
+
+
+def solo_adamw_step(param, grad, m_codes, m_scale, v_codes, v_scale, v_base, n, step, cfg,
+                    stream=None, check=True):
+    rc = lib().solo_adamw_step(_ptr(param), _ptr(grad), _ptr(m_codes), _ptr(m_scale),
+                               _ptr(v_codes), _ptr(v_scale), _ptr(v_base), n, step,
+                               C.byref(cfg), _stream(stream) if n else None)
+    if check and rc != SOLO_OK:
+        raise SoloError(rc)
+    return rc
+
+
+class SoloState:
+    """Device buffers of the packed optimizer state of n elements (caller-owned memory:
+    plain torch tensors; int32 tensors carry the uint32 code words)."""
+
+    def __init__(self, n, cfg, device="cuda", init=True):
+        import torch
+        self.n, self.cfg = n, cfg
+        nb = solo_num_blocks(n, cfg.block_size)
+        self.m_codes = torch.empty(solo_code_words(n, cfg.bits_m), dtype=torch.int32, device=device)
+        self.v_codes = torch.empty(solo_code_words(n, cfg.bits_v), dtype=torch.int32, device=device)
+        self.m_scale = torch.empty(nb, dtype=torch.float32, device=device)
+        self.v_scale = torch.empty(nb, dtype=torch.float32, device=device)
+        self.v_base = torch.empty(nb, dtype=torch.float32, device=device)
+        if init:
+            solo_state_init(self.m_codes, self.m_scale, self.v_codes, self.v_scale, self.v_base,
+                            n, cfg)
+
+    def buffers(self):
+        return (self.m_codes, self.m_scale, self.v_codes, self.v_scale, self.v_base)
+
+    def step(self, param, grad, step, stream=None):
+        return solo_adamw_step(param, grad, *self.buffers(), self.n, step, self.cfg, stream)

@@ -1,0 +1,121 @@
+"""Host-side checks of libsolo that need no GPU: the library loads, exports every symbol that
+include/solo.h declares, and its pure host helpers agree with the paper's printed values."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT, read_golden
+
+
+@pytest.fixture(scope="module")
+def solo():
+    from paper_2505_00347_amd import solo as s
+    if not os.path.exists(s.LIB_PATH):
+        from paper_2505_00347_amd import build
+        build.build(force=True)
+    s.lib()
+    return s
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "solo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(solo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(solo):
+    names = declared_functions()
+    assert {"solo_adamw_step", "solo_state_init", "solo_code_words", "solo_num_blocks",
+            "solo_state_bytes", "solo_beta1_default", "solo_beta1_bound", "solo_strerror"} <= set(names)
+    raw = ctypes.CDLL(solo.LIB_PATH)
+    for name in names:
+        assert hasattr(raw, name), name
+
+
+def test_config_struct_matches_header(solo):
+    """Field order and sizes of the ctypes mirror follow the C declaration."""
+    text = open(os.path.join(ROOT, "include", "solo.h")).read()
+    body = re.search(r"typedef struct solo_config \{(.*?)\} solo_config;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            typ, names = decl.split(None, 1)
+            fields += [(n.strip(), typ) for n in names.split(",")]
+    ctype = {"uint32_t": ctypes.c_uint32, "uint64_t": ctypes.c_uint64, "float": ctypes.c_float}
+    assert [(n, ctype[t]) for n, t in fields] == list(solo.solo_config._fields_)
+    assert ctypes.sizeof(solo.solo_config) == 64
+
+
+def test_size_queries(solo):
+    assert solo.solo_code_words(2560, 2) == 160 and solo.solo_code_words(2560, 3) == 256
+    assert solo.solo_code_words(2560, 4) == 320 and solo.solo_code_words(11, 3) == 2
+    assert solo.solo_code_words(0, 4) == 0 and solo.solo_code_words(100, 5) == 0
+    assert solo.solo_num_blocks(129, 128) == 2 and solo.solo_num_blocks(0, 64) == 0
+    # Sec. 4.2: the scale costs 1/4 bit per element at block 128 and the buffered base
+    # doubles it: (b_m + b_v)/8 + 12/B bytes per parameter
+    n = 128 * 2560
+    cfg = solo.make_config(2, 2, 128)
+    assert solo.solo_state_bytes(n, cfg) == n * (2 + 2) // 8 + 12 * n // 128
+    cfg = solo.make_config(4, 3, 64)
+    assert solo.solo_state_bytes(n, cfg) == n * 4 // 8 + 4 * n // 10 + 12 * n // 64
+    # the memory table of the paper (LLaMA-7B): SOLO 2-bit AdamW holds 3.61 GB, 0.20 GB more
+    # than 2-bit AdamW without a buffered base (3.41 GB): one float per block of 128
+    n7b = 6738415616
+    total = solo.solo_state_bytes(n7b, solo.make_config(2, 2, 128))
+    without_base = n7b * 4 // 8 + 8 * (n7b // 128)
+    assert abs((total - without_base) / 2 ** 30 - (3.61 - 3.41)) < 0.006
+    assert abs(total / 2 ** 30 - 3.61) < 0.15
+
+
+def test_beta1_defaults(solo):
+    """Sec. 3.4: 0.8 / 0.3 for 4-bit, 0.5 / 0.1 for 2-bit first moments."""
+    assert solo.solo_beta1_default(4, 0) == pytest.approx(0.8) and solo.solo_beta1_default(4, 1) == pytest.approx(0.3)
+    assert solo.solo_beta1_default(2, 0) == pytest.approx(0.5) and solo.solo_beta1_default(2, 1) == pytest.approx(0.1)
+    assert solo.solo_beta1_default(3, 0) == pytest.approx(0.6) and solo.solo_beta1_default(3, 1) == pytest.approx(0.2)
+
+
+def test_beta_prime_bound_reproduces_the_papers_table(solo):
+    rows = read_golden("beta_prime_table.txt")
+    rmed = {int(r[1]): float(r[2]) for r in rows if r[0] == "rmed"}
+    bounds = [(int(r[1]), int(r[2]), float(r[3])) for r in rows if r[0] == "bound"]
+    assert len(bounds) == 12
+    for bprime, b, want in bounds:
+        got = solo.solo_beta1_bound(0.9, rmed[b], rmed[bprime])
+        assert abs(got - want) < 6e-4, (bprime, b, got, want)
+    # the paper's defaults sit just under the b = 5 (fine-tuning) and b = 8 (scratch) columns
+    assert solo.solo_beta1_default(4, 0) <= solo.solo_beta1_bound(0.9, rmed[5], rmed[4])
+    assert solo.solo_beta1_default(2, 0) <= solo.solo_beta1_bound(0.9, rmed[5], rmed[2])
+    assert solo.solo_beta1_default(4, 1) <= solo.solo_beta1_bound(0.9, rmed[8], rmed[4])
+    assert solo.solo_beta1_default(2, 1) <= solo.solo_beta1_bound(0.9, rmed[8], rmed[2])
+    assert solo.solo_beta1_bound(1.5, 0.1, 0.1) == 0.0
+
+
+def test_error_strings_and_host_side_rejections(solo):
+    assert "success" in solo.solo_strerror(0)
+    for code in (-1, -2, -3, -99):
+        assert solo.solo_strerror(code)
+    cfg = solo.make_config(2, 3, 128, 1)
+    # rejected on the host before any HIP call: works without a GPU
+    assert solo.solo_adamw_step(0, 0, 0, 0, 0, 0, 0, 100, 1, cfg, stream=0, check=False) == solo.SOLO_E_INVALID
+    assert solo.solo_adamw_step(0, 0, 0, 0, 0, 0, 0, 0, 1, cfg, stream=0, check=False) == solo.SOLO_OK
+    bad = solo.make_config(2, 3, 100, 1)
+    assert solo.solo_state_init(16, 16, 16, 16, 16, 100, bad, stream=0, check=False) == solo.SOLO_E_INVALID
+
+
+def test_product_does_not_import_the_oracle():
+    """The library and its binding must not reach into oracle/ (tests, smoke and the
+    benchmark's cpu_baseline leg are the only users)."""
+    pkg = os.path.join(ROOT, "paper_2505_00347_amd")
+    for base, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(base, f)).read()
+                assert "oracle" not in text.lower() or f == "synth.py", f
+    text = open(os.path.join(pkg, "synth.py")).read()
+    assert "import oracle" not in text and "from oracle" not in text
+    src = open(os.path.join(ROOT, "oracle", "solo_oracle.py")).read() + open(os.path.join(ROOT, "oracle", "solo_oracle.c")).read()
+    assert "paper_2505_00347_amd" not in src and "solo.h" not in src

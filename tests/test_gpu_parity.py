@@ -1,0 +1,323 @@
+"""GPU parity: the HIP library (through its C-ABI) against the CPU oracle.
+
+Both sides receive the same seeded inputs.  The bar, per step:
+  * block scales Delta_m, Delta_v and bases alpha: bit-exact;
+  * 1st-moment code words: bit-exact;
+  * 2nd-moment codes: equal, except +-1 flips where the oracle's own binary64
+    margin to the rounding boundary is below FLIP_MARGIN (the two sides use
+    different log2 routines); at most 1e-5 of the elements;
+  * parameters: |dp| <= 1e-6 |p| + 1e-9 after one step from equal states, and
+    <= 1e-5 |p| + 1e-5 lr after ten free-running steps (a parameter can be
+    arbitrarily close to zero while every step moves it by O(lr)).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+FLIP_MARGIN = 5e-5
+FLIP_RATE = 1e-5
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_00347_amd import solo
+    solo.lib()                       # fails loudly if the library is not built
+    return solo
+
+
+def dev(x):
+    import torch
+    if x.dtype == np.uint32:
+        return torch.from_numpy(x.view(np.int32)).cuda()
+    if x.dtype == np.uint16:        # bf16 bit patterns
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+def host_words(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+class GpuSide:
+    """Device copy of (param, state) plus the C-ABI calls."""
+
+    def __init__(self, solo, n, cfg):
+        self.solo, self.n, self.cfg = solo, n, cfg
+        self.state = solo.SoloState(n, cfg)
+        self.p = None
+
+    def load(self, p, st):
+        self.p = dev(p)
+        s = self.state
+        s.m_codes.copy_(dev(st.m_words)); s.v_codes.copy_(dev(st.v_words))
+        s.m_scale.copy_(dev(st.m_scale)); s.v_scale.copy_(dev(st.v_scale)); s.v_base.copy_(dev(st.v_base))
+
+    def step(self, g_dev, step):
+        self.state.step(self.p, g_dev, step)
+
+    def fetch(self):
+        import torch
+        torch.cuda.synchronize()
+        s = self.state
+        return (self.p.cpu().numpy(), host_words(s.m_codes), s.m_scale.cpu().numpy(),
+                host_words(s.v_codes), s.v_scale.cpu().numpy(), s.v_base.cpu().numpy())
+
+
+def make_cfgs(so, solo, bm, bv, B, bf16=False, stochastic=1, beta1=None, p=0.1, seed=42, off=0,
+              lr=1e-3, wd=0.01, eps=1e-8, beta2=0.999):
+    beta1 = {2: 0.5, 3: 0.6, 4: 0.8}[bm] if beta1 is None else beta1
+    oc = so.make_config(bits_m=bm, bits_v=bv, block_size=B, stochastic=stochastic, lr=lr, beta1=beta1,
+                        beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p, seed=seed, index_offset=off)
+    gc = solo.make_config(bits_m=bm, bits_v=bv, block_size=B, grad_dtype=1 if bf16 else 0, lr=lr,
+                          beta1=beta1, beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p,
+                          flags=1 if stochastic else 0, seed=seed, index_offset=off)
+    return oc, gc
+
+
+def bits_equal(a, b):
+    return np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainted=None):
+    """Compare one step's results; returns the number of v-code flips.  `tainted` (bool per
+    block, updated in place) marks blocks whose state already differs legitimately."""
+    B = oc.block_size
+    gp, gm, gms, gv, gvs, gva = got
+    nblk = want_st.m_scale.size
+    clean = np.ones(nblk, bool) if tainted is None else ~tainted
+    eclean = np.repeat(clean, B)[:n]
+    assert bits_equal(gms[clean], want_st.m_scale[clean]), "Delta_m differs"
+    assert bits_equal(gvs[clean], want_st.v_scale[clean]), "Delta_v differs"
+    assert bits_equal(gva[clean], want_st.v_base[clean]), "alpha differs"
+    wm, wv = so.unpack(want_st.m_words, n, oc.bits_m), so.unpack(want_st.v_words, n, oc.bits_v)
+    hm, hv = so.unpack(gm, n, oc.bits_m), so.unpack(gv, n, oc.bits_v)
+    assert np.array_equal(hm[eclean], wm[eclean]), "1st-moment codes differ"
+    if tainted is None:
+        assert np.array_equal(gm, want_st.m_words), "1st-moment words differ (pad bits?)"
+    diff = np.nonzero((hv != wv) & eclean)[0]
+    if diff.size:
+        d = np.abs(hv[diff].astype(int) - wv[diff].astype(int))
+        assert d.max() == 1, f"2nd-moment code off by {d.max()} at {diff[np.argmax(d)]}"
+        assert margin[diff].max() < FLIP_MARGIN, \
+            f"2nd-moment flip away from a tie: margin {margin[diff].max():.3g} at {diff[np.argmax(margin[diff])]}"
+        if tainted is not None:
+            tainted[np.unique(diff // B)] = True
+    elif tainted is None:
+        assert np.array_equal(gv, want_st.v_words), "2nd-moment words differ (pad bits?)"
+    err = np.abs(gp.astype(np.float64) - want_p)
+    tol = p_rtol * np.abs(want_p) + p_atol
+    bad = (err > tol) & eclean
+    assert not bad.any(), f"parameter error {err[bad].max():.3g} at {np.nonzero(bad)[0][0]}"
+    return diff.size
+
+
+def grads_for(kind, n, std, seed, bf16):
+    from paper_2505_00347_amd import synth
+    g = synth.make_grads(n, kind, std, seed)
+    if bf16:
+        bits, g = synth.round_to_bf16(g)
+        return g, dev(bits)
+    return g, dev(g)
+
+
+def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal", std=1e-3,
+                       seed0=100, **kw):
+    from paper_2505_00347_amd import synth
+    oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
+    p = synth.make_params(n)
+    st = so.State(n, oc)
+    side = GpuSide(solo, n, gc)
+    flips = 0
+    for step in range(1, steps + 1):
+        g, g_dev = grads_for(kind, n, std, seed0 + step, bf16)
+        side.load(p, st)
+        side.step(g_dev, step)
+        margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
+        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 1e-9)
+    assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
+    return flips
+
+
+def run_free(so, solo, n, bm, bv, B, bf16=False, steps=10, kind="normal", std=1e-3, seed0=100, **kw):
+    from paper_2505_00347_amd import synth
+    oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
+    p = synth.make_params(n)
+    st = so.State(n, oc)
+    side = GpuSide(solo, n, gc)
+    side.p = dev(p)
+    got = side.fetch()                       # solo_state_init against the oracle's zero state
+    assert np.array_equal(got[1], st.m_words) and np.array_equal(got[3], st.v_words)
+    assert bits_equal(got[2], st.m_scale) and bits_equal(got[4], st.v_scale) and bits_equal(got[5], st.v_base)
+    tainted = np.zeros(st.m_scale.size, bool)
+    flips = 0
+    for step in range(1, steps + 1):
+        g, g_dev = grads_for(kind, n, std, seed0 + step, bf16)
+        side.step(g_dev, step)
+        margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
+        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-5, 1e-5 * oc.lr, tainted)
+    assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
+    assert tainted.mean() <= max(2.0 / tainted.size, 2 * FLIP_RATE * B * steps)
+    return flips, int(tainted.sum())
+
+
+# ------------------------------------------------------------ the named configs
+
+def test_config1_4bit_normal_ten_steps(so, gpu):
+    """2^20 parameters, 4-bit m + 4-bit log v, block 128, beta1 0.8, N(0,1e-3) gradients."""
+    run_teacher_forced(so, gpu, 1 << 20, 4, 4, 128, steps=10, seed0=1000)
+    flips, tainted = run_free(so, gpu, 1 << 20, 4, 4, 128, steps=10, seed0=1000)
+    print(f"config 1 free-running: {flips} flips, {tainted} blocks diverged")
+
+
+def test_config2_3bit_student_t_ten_steps(so, gpu):
+    """Same tensor, 3-bit states (ten codes per word), heavy-tailed Student-t(3) gradients."""
+    run_teacher_forced(so, gpu, 1 << 20, 3, 3, 128, steps=10, kind="student_t3", seed0=2000)
+    flips, tainted = run_free(so, gpu, 1 << 20, 3, 3, 128, steps=10, kind="student_t3", seed0=2000)
+    print(f"config 2 free-running: {flips} flips, {tainted} blocks diverged")
+
+
+def test_config3_shape_2bit_block64(so, gpu):
+    """GPT-2-125M-shaped: a slice of a matrix plus LayerNorm-sized vectors (768), 2-bit, B=64."""
+    run_teacher_forced(so, gpu, 768 * 2304 // 4, 2, 2, 64, steps=4, seed0=3000)
+    run_free(so, gpu, 768, 2, 2, 64, steps=10, seed0=3100)           # a LayerNorm vector
+    run_free(so, gpu, 50257 * 8, 2, 2, 64, steps=5, seed0=3200)      # odd vocabulary rows: ragged tail
+
+
+def test_config4_shape_3bit_bf16_outliers(so, gpu):
+    """1.3B-shaped slice: bf16 gradients N(0,1e-4) with 1 % outliers x100, 3-bit, B=128."""
+    run_teacher_forced(so, gpu, 2048 * 1024, 3, 3, 128, bf16=True, steps=4, kind="normal_outliers",
+                       std=1e-4, seed0=4000)
+    run_free(so, gpu, 2048 * 256 + 2048, 3, 3, 128, bf16=True, steps=10, kind="normal_outliers",
+             std=1e-4, seed0=4100)
+
+
+def test_config5_shape_2bit_m_3bit_v_bf16(so, gpu):
+    """LLaMA-7B-shaped slice: 2-bit m, 3-bit log v, bf16 gradients, B=128."""
+    run_teacher_forced(so, gpu, 4096 * 1024, 2, 3, 128, bf16=True, steps=4, kind="normal_outliers",
+                       std=1e-4, seed0=5000)
+    run_free(so, gpu, 4096 * 96 + 4096, 2, 3, 128, bf16=True, steps=10, kind="normal_outliers",
+             std=1e-4, seed0=5100)
+
+
+# ------------------------------------------------------ every format, ragged sizes
+
+@pytest.mark.parametrize("bm", (2, 3, 4))
+@pytest.mark.parametrize("bv", (2, 3, 4))
+def test_all_formats(so, gpu, bm, bv):
+    for B, bf16, n in ((128, False, 3 * 2560 + 777), (64, True, 2 * 2560 + 1283)):
+        run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
+
+
+@pytest.mark.parametrize("n", (1, 7, 8, 9, 63, 64, 65, 127, 128, 129, 641, 2559, 2560, 2561, 5120, 7681))
+def test_ragged_sizes(so, gpu, n):
+    run_free(so, gpu, n, 2, 3, 128, bf16=True, steps=3, std=1e-4, seed0=n)
+    run_free(so, gpu, n, 3, 4, 64, steps=3, seed0=n + 1)
+
+
+def test_quantile_settings_and_nearest_rounding(so, gpu):
+    n = 4 * 2560 + 300
+    for p in (0.0, 0.05, 0.3, 0.5):
+        run_teacher_forced(so, gpu, n, 4, 2, 128, steps=3, p=p, seed0=int(p * 100))
+        run_teacher_forced(so, gpu, n, 2, 3, 64, steps=3, p=p, seed0=int(p * 100) + 1)
+    run_teacher_forced(so, gpu, n, 3, 3, 128, steps=4, stochastic=0, seed0=77)
+    run_free(so, gpu, n, 2, 4, 128, steps=6, stochastic=0, seed0=78)
+
+
+def test_index_offset_and_seed(so, gpu):
+    run_teacher_forced(so, gpu, 6000, 2, 3, 128, steps=3, off=8 * (1 << 33) + 2560 * 7, seed=123456789)
+    run_teacher_forced(so, gpu, 6000, 4, 4, 64, steps=3, off=8, seed=0)
+
+
+def test_hyperparameter_ranges(so, gpu):
+    run_teacher_forced(so, gpu, 5000, 4, 4, 128, steps=3, beta1=0.0, beta2=0.0, lr=1e-2, wd=0.0, eps=1e-6)
+    run_teacher_forced(so, gpu, 5000, 2, 2, 128, steps=3, beta1=0.1, beta2=0.98, lr=3e-4, wd=0.1)
+    run_teacher_forced(so, gpu, 5000, 3, 3, 64, steps=3, std=30.0)            # large gradients
+    run_teacher_forced(so, gpu, 5000, 3, 3, 64, steps=3, std=1e-9, bf16=True)  # tiny gradients
+
+
+# ------------------------------------------------------------ degenerate inputs
+
+def special_grads(n, B, seed):
+    rng = np.random.default_rng(seed)
+    g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g[0 * B:1 * B] = 0                         # all-zero block
+    g[1 * B:2 * B] = 2e-3                      # constant block
+    g[2 * B:3 * B] = -2e-3
+    g[3 * B + 5:4 * B] = 0                     # sparse block: x_p = 0
+    g[4 * B:5 * B] = np.where(rng.random(B) < 0.5, 1e-3, -1e-3)   # equal magnitudes: all ties
+    g[5 * B:6 * B] = 1e-18                     # underflows to the zero block
+    g[6 * B:7 * B:2] = 0                       # half zeros
+    return g
+
+
+@pytest.mark.parametrize("bm,bv,B,bf16", [(2, 3, 128, False), (4, 4, 64, False), (3, 2, 128, True)])
+def test_degenerate_blocks(so, gpu, bm, bv, B, bf16):
+    from paper_2505_00347_amd import synth
+    n = 24 * B + 11
+    oc, gc = make_cfgs(so, gpu, bm, bv, B, bf16)
+    p = synth.make_params(n)
+    st = so.State(n, oc)
+    side = GpuSide(gpu, n, gc)
+    for step in range(1, 9):
+        g = special_grads(n, B, step) if step != 5 else np.zeros(n, np.float32)   # one all-zero step
+        if step in (6, 7):
+            g[: 8 * B] = 0                                                         # rows that stay idle
+        if bf16:
+            bits, g = synth.round_to_bf16(g)
+            g_dev = dev(bits)
+        else:
+            g_dev = dev(g)
+        side.load(p, st)
+        side.step(g_dev, step)
+        margin = so.step_packed(p, g, st, step, oc, want_margin=True)
+        compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 1e-9)
+        assert np.all(np.isfinite(p))
+
+
+def test_empty_and_invalid_arguments(gpu):
+    import torch
+    solo = gpu
+    cfg = solo.make_config(2, 3, 128, 1)
+    p = torch.zeros(2560, device="cuda")
+    g = torch.zeros(2560, device="cuda", dtype=torch.bfloat16)
+    st = solo.SoloState(2560, cfg)
+    args = (p, g, *st.buffers())
+    assert solo.solo_adamw_step(*args, 0, 1, cfg, check=False) == solo.SOLO_OK          # n = 0
+    assert solo.solo_adamw_step(*args, 2560, 0, cfg, check=False) == solo.SOLO_E_INVALID  # step 0
+    assert solo.solo_adamw_step(p.data_ptr() + 4, g, *st.buffers(), 2560, 1, cfg, check=False) == solo.SOLO_E_INVALID
+    assert solo.solo_adamw_step(0, g, *st.buffers(), 2560, 1, cfg, check=False) == solo.SOLO_E_INVALID
+    for field, value in (("bits_m", 5), ("bits_v", 1), ("block_size", 96), ("grad_dtype", 2),
+                         ("beta1", 1.0), ("beta2", -0.1), ("quantile_p", 1.0), ("eps", -1.0),
+                         ("flags", 2), ("reserved", 1), ("index_offset", 4), ("lr", float("nan"))):
+        bad = solo.make_config(2, 3, 128, 1)
+        setattr(bad, field, value)
+        assert solo.solo_adamw_step(*args, 2560, 1, bad, check=False) == solo.SOLO_E_INVALID, field
+        assert solo.solo_state_init(*st.buffers(), 2560, bad, check=False) == solo.SOLO_E_INVALID, field
+    torch.cuda.synchronize()
+    assert torch.all(p == 0)                                # nothing was enqueued by the failed calls
+    with pytest.raises(solo.SoloError):
+        solo.solo_adamw_step(*args, 2560, 0, cfg)
+
+
+def test_runs_on_the_callers_stream(so, gpu):
+    import torch
+    from paper_2505_00347_amd import synth
+    n = 3 * 2560 + 100
+    oc, gc = make_cfgs(so, gpu, 4, 4, 128)
+    p = synth.make_params(n)
+    g = synth.make_grads(n, "normal", 1e-3, 5)
+    st = so.State(n, oc)
+    side = GpuSide(gpu, n, gc)
+    side.load(p, st)
+    g_dev = dev(g)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        side.state.step(side.p, g_dev, 1)          # binding picks up the current stream
+    s.synchronize()
+    margin = so.step_packed(p, g, st, 1, oc, want_margin=True)
+    compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 1e-9)
