@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused SOLO AdamW step on one MI355X.
+
+One "step" is one call of solo_adamw_step over the whole flat buffer of a workload:
+dequantize both moments, both EMAs, the parameter update, block statistics, re-quantize,
+re-pack, with every input already resident in HBM.  Default workload: the LLaMA-7B-shaped
+tensor set (6,738,415,616 fp32 parameters, bf16 gradients, 2-bit m, 3-bit log v, block 128).
+
+Prints ONE JSON line: updated parameters per second, the HBM roofline of the step kernel
+(algorithmic bytes / HIP-event duration of the launches on their own stream), and the CPU
+oracle timed on the host cores of this machine on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X: 8 TB/s HBM3E
+
+
+def bytes_per_param(w):
+    """Algorithmic HBM bytes per parameter and step: read p, g, both code streams and three
+    block scalars; write p, both code streams and three block scalars.  A 3-bit code costs
+    3.2 bits (ten per 32-bit word)."""
+    stored = {2: 2.0, 3: 3.2, 4: 4.0}
+    g = 2 if w.grad_dtype == "bf16" else 4
+    codes = (stored[w.bits_m] + stored[w.bits_v]) / 8.0
+    scales = 12.0 / w.block_size
+    return (4 + g + codes + scales) + (4 + codes + scales)
+
+
+def device_grads(torch, n, kind, std, seed, dtype):
+    """Seeded synthetic gradients generated on the device, chunk by chunk (same recipe as
+    synth.make_grads: N(0, std^2), Student-t(3) * std, or normal with 1 % of entries x100)."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    out = torch.empty(n, dtype=dtype, device="cuda")
+    chunk = 1 << 27
+    for a in range(0, n, chunk):
+        b = min(n, a + chunk)
+        x = torch.randn(b - a, device="cuda", generator=gen)
+        if kind == "normal_outliers":
+            mask = torch.rand(b - a, device="cuda", generator=gen) < 0.01
+            x = torch.where(mask, x * 100.0, x)
+        elif kind == "student_t3":
+            chi = torch.randn(3, b - a, device="cuda", generator=gen).square_().sum(0).div_(3.0).sqrt_()
+            x = x / chi
+        out[a:b] = (x * std).to(dtype)
+    return out
+
+
+def device_params(torch, w, seed):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    p = torch.empty(w.n, dtype=torch.float32, device="cuda")
+    pos = 0
+    chunk = 1 << 27
+    for _, numel, kind in w.tensors:
+        if kind == "ones":
+            p[pos:pos + numel] = 1.0
+        elif kind == "zeros":
+            p[pos:pos + numel] = 0.0
+        else:
+            for a in range(pos, pos + numel, chunk):
+                b = min(pos + numel, a + chunk)
+                p[a:b] = torch.randn(b - a, device="cuda", generator=gen) * 0.02
+        pos += numel
+    return p
+
+
+def cpu_baseline(w, sample, steps=3):
+    """The CPU oracle, as it stands, on the first `sample` elements of the workload's largest
+    tensor class, all host threads, median of the timed steps."""
+    import numpy as np
+    from oracle import solo_oracle as so
+    from paper_2505_00347_amd import synth
+    threads = min(so.max_threads(), int(os.environ.get("OMP_NUM_THREADS", "1000")))
+    cfg = so.make_config(bits_m=w.bits_m, bits_v=w.bits_v, block_size=w.block_size, beta1=w.beta1,
+                         beta2=w.beta2, lr=w.lr, eps=w.eps, weight_decay=w.weight_decay,
+                         quantile_p=w.quantile_p, seed=synth.SEED_XI)
+    p = synth.make_params(sample)
+    st = so.State(sample, cfg)
+    times = []
+    for step in range(1, steps + 1):
+        g = synth.make_grads(sample, w.grad_kind, w.grad_std, synth.seed_grad(w.config_id, step))
+        if w.grad_dtype == "bf16":
+            g = synth.round_to_bf16(g)[1]
+        t0 = time.perf_counter()
+        so.step_packed(p, g, st, step, cfg, threads=threads)
+        times.append(time.perf_counter() - t0)
+    t = float(np.median(times[1:])) if len(times) > 1 else times[0]
+    return {"value": sample / t, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample} elements of the workload (one contiguous slice, packed "
+                      f"states, {steps} steps, median of steps 2..{steps}); the step is block-local, "
+                      "so the rate carries over to the full tensor set"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5_llama7b_2bit_3bit")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 26)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
+                 "multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2505_00347_amd import solo, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    solo.lib()
+    w = synth.workload(args.workload)
+    n = w.n
+    cfg = solo.make_config(w.bits_m, w.bits_v, w.block_size,
+                           solo.SOLO_GRAD_BF16 if w.grad_dtype == "bf16" else solo.SOLO_GRAD_FP32,
+                           lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                           weight_decay=w.weight_decay, quantile_p=w.quantile_p, seed=synth.SEED_XI)
+    gdtype = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    p = device_params(torch, w, synth.SEED_PARAM)
+    grads = [device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(w.config_id, k), gdtype)
+             for k in (1, 2)]
+    state = solo.SoloState(n, cfg)
+    torch.cuda.synchronize()
+
+    step = 0
+    for _ in range(args.warmup):
+        step += 1
+        state.step(p, grads[step & 1], step)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step += 1
+        starts[k].record()                      # same stream as the launch (torch's current)
+        state.step(p, grads[step & 1], step)
+        ends[k].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    assert bool(torch.isfinite(p[:1 << 20]).all())
+
+    ms_per_step = wall / args.steps * 1e3
+    bpp = bytes_per_param(w)
+    achieved = bpp * n / avg_kernel_s / 1e9
+    out = {
+        "metric": "updated_params_per_sec", "value": n / (wall / args.steps), "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "params": n, "bits_m": w.bits_m, "bits_v": w.bits_v,
+                   "block_size": w.block_size, "grad_dtype": w.grad_dtype, "beta1": w.beta1,
+                   "bytes_per_param": bpp},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3},
+    }
+    del grads, p, state
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_sample, n))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -6,9 +6,11 @@ Both sides receive the same seeded inputs.  The bar, per step:
   * 2nd-moment codes: equal, except +-1 flips where the oracle's own binary64
     margin to the rounding boundary is below FLIP_MARGIN (the two sides use
     different log2 routines); at most 1e-5 of the elements;
-  * parameters: |dp| <= 1e-6 |p| + 1e-9 after one step from equal states, and
+  * parameters: |dp| <= 1e-6 |p| + 2e-6 lr after one step from equal states, and
     <= 1e-5 |p| + 1e-5 lr after ten free-running steps (a parameter can be
-    arbitrarily close to zero while every step moves it by O(lr)).
+    arbitrarily close to zero while every step moves it by O(lr); the kernel's
+    sqrt and reciprocal are good to 1 ulp, so one step is off by ~1e-7 of its
+    own size plus the rounding of p).
 """
 import numpy as np
 import pytest
@@ -137,7 +139,7 @@ def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal
         side.load(p, st)
         side.step(g_dev, step)
         margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
-        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 1e-9)
+        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
     assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
     return flips
 
@@ -274,7 +276,7 @@ def test_degenerate_blocks(so, gpu, bm, bv, B, bf16):
         side.load(p, st)
         side.step(g_dev, step)
         margin = so.step_packed(p, g, st, step, oc, want_margin=True)
-        compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 1e-9)
+        compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
         assert np.all(np.isfinite(p))
 
 
@@ -320,4 +322,81 @@ def test_runs_on_the_callers_stream(so, gpu):
         side.state.step(side.p, g_dev, 1)          # binding picks up the current stream
     s.synchronize()
     margin = so.step_packed(p, g, st, 1, oc, want_margin=True)
-    compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 1e-9)
+    compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
+
+
+# ---------------------------------- the benchmark's workload at its full size, sampled
+
+def test_full_size_7b_workload_sampled_tiles(so, gpu):
+    """The LLaMA-7B-shaped workload exactly as bench.py launches it (6,738,415,616 elements,
+    one call).  The oracle cannot run 6.7e9 elements in seconds, so the third step is checked
+    on sampled 2560-element super-tiles (first, last full, the ragged tail, tensor boundaries
+    and random ones): inputs of those slices are copied out before the step, the oracle runs
+    on each slice with the slice's global offset, and every output byte of the slice is
+    compared.  Properties that hold at any size are checked on the whole buffer."""
+    import torch
+    import bench
+    from paper_2505_00347_amd import synth
+    solo = gpu
+    free, _ = torch.cuda.mem_get_info()
+    w = synth.workload("c5_llama7b_2bit_3bit")
+    n = w.n
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs 60 GiB of free HBM")
+    oc, gc = make_cfgs(so, solo, w.bits_m, w.bits_v, w.block_size, bf16=True, beta1=w.beta1)
+    p = bench.device_params(torch, w, synth.SEED_PARAM)
+    state = solo.SoloState(n, gc)
+    for step in (1, 2):
+        g = bench.device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(5, step), torch.bfloat16)
+        state.step(p, g, step)
+        del g
+    g = bench.device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(5, 3), torch.bfloat16)
+    T = 2560
+    n_tiles = n // T
+    rng = np.random.default_rng(0)
+    tiles = {0, 1, n_tiles - 1, n_tiles}                         # n_tiles = the ragged tail
+    pos = 0
+    for _, numel, _ in w.tensors[:12]:                           # tiles that straddle tensors
+        pos += numel
+        tiles.add(pos // T)
+    tiles |= set(int(t) for t in rng.integers(0, n_tiles, 40))
+    tiles = sorted(tiles)
+
+    def grab(t):
+        a, b = t * T, min(n, (t + 1) * T)
+        cnt = b - a
+        st = so.State(cnt, oc)
+        st.m_words[:] = host_words(state.m_codes[a // 16:a // 16 + st.m_words.size])
+        st.v_words[:] = host_words(state.v_codes[a // 10:a // 10 + st.v_words.size])
+        nb = st.m_scale.size
+        st.m_scale[:] = state.m_scale[a // 128:a // 128 + nb].cpu().numpy()
+        st.v_scale[:] = state.v_scale[a // 128:a // 128 + nb].cpu().numpy()
+        st.v_base[:] = state.v_base[a // 128:a // 128 + nb].cpu().numpy()
+        return a, cnt, p[a:b].cpu().numpy(), g[a:b].float().cpu().numpy(), st
+
+    before = [grab(t) for t in tiles]
+    assert float(state.v_base.min()) > 0 and float(state.v_base.max()) <= 1
+    state.step(p, g, 3)
+    torch.cuda.synchronize()
+    flips = 0
+    for a, cnt, p0, g0, st in before:
+        cfg_t = so.make_config(bits_m=2, bits_v=3, block_size=128, beta1=w.beta1, index_offset=a)
+        margin = so.step_packed(p0, g0, st, 3, cfg_t, want_margin=True)
+        nb = st.m_scale.size
+        got = (p[a:a + cnt].cpu().numpy(),
+               host_words(state.m_codes[a // 16:a // 16 + st.m_words.size]),
+               state.m_scale[a // 128:a // 128 + nb].cpu().numpy(),
+               host_words(state.v_codes[a // 10:a // 10 + st.v_words.size]),
+               state.v_scale[a // 128:a // 128 + nb].cpu().numpy(),
+               state.v_base[a // 128:a // 128 + nb].cpu().numpy())
+        flips += compare_step(so, oc, cnt, p0, st, margin, got, 1e-6, 2e-6 * oc.lr)
+    assert flips <= 2
+    # whole-buffer properties: codes in range, pad bits zero, scales finite and ordered
+    vw = state.v_codes
+    assert int((vw >> 30).abs().max()) == 0                      # two pad bits of every 3-bit word
+    mw = state.m_codes
+    both = mw & (mw >> 1) & 0x55555555                           # a 2-bit field equal to 3 is never produced
+    assert int(both.abs().max()) == 0
+    assert bool(torch.isfinite(state.m_scale).all()) and bool(torch.isfinite(state.v_scale).all())
+    assert float(state.v_base.min()) >= 2.0 ** (-64 / 7) * (1 - 1e-6) and float(state.v_base.max()) <= 1
+    assert bool(torch.isfinite(p[:: 4099]).all())
