@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--workload", default="c5_llama7b_2bit_3bit")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed steps, copy the parameter buffer once (a plain copy of "
+                         "known size that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
@@ -150,6 +153,11 @@ def main():
     kernel_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
     avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     assert bool(torch.isfinite(p[:1 << 20]).all())
+    if args.copy_probe:
+        probe = torch.empty_like(p)
+        probe.copy_(p)                           # reads 4n bytes, writes 4n bytes
+        torch.cuda.synchronize()
+        del probe
 
     ms_per_step = wall / args.steps * 1e3
     bpp = bytes_per_param(w)

@@ -152,12 +152,13 @@ uint32_t so_xi_bits(const uint32_t keys[4], uint64_t i)
     return X + j * Y;
 }
 
-/* xi in the open interval (-0.5, 0.5): the top 24 bits u give
- * (u + 0.5) / 2^24 - 0.5, which binary32 holds exactly. */
+/* xi in the open interval (-0.5, 0.5): the top 23 bits u give
+ * (u + 0.5) / 2^23 - 0.5, which binary32 holds exactly (23 bits are what fits
+ * the fraction field of a binary32 in [1, 2)). */
 float so_xi(const uint32_t keys[4], uint64_t i)
 {
-    uint32_t u = so_xi_bits(keys, i) >> 8;
-    return (float)u * 0x1p-24f + (0x1p-25f - 0.5f);
+    uint32_t u = so_xi_bits(keys, i) >> 9;
+    return (float)u * 0x1p-23f + (0x1p-24f - 0.5f);
 }
 
 /* -------------------------------------------------------------- quantizers */

@@ -281,8 +281,8 @@ def test_xi_stream_is_uniform_and_uncorrelated(so):
     assert corr(a, b) < lim and corr(a, c) < lim                      # across steps and seeds
     assert abs(far.mean()) < 5 * math.sqrt(1 / 12 / 4096)
     assert not np.array_equal(far, a[:4096])
-    # (u + 1/2)/2^24 - 1/2 exactly: xi * 2^25 is an odd integer
-    k = a * 2.0 ** 25
+    # (u + 1/2)/2^23 - 1/2 exactly: xi * 2^24 is an odd integer
+    k = a * 2.0 ** 24
     assert np.all(k == np.rint(k)) and np.all(np.mod(k, 2) == 1)
     # pure function of (seed, step, index)
     assert so.xi(so.xi_keys(42, 1), 12345) == np.float32(a[12345])
