@@ -176,9 +176,7 @@ int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_
     const uint64_t z = cfg->seed + gamma * step;
     const uint64_t ka = solo::mix64(z + gamma), kb = solo::mix64(z + 2 * gamma);
     a.key0 = (uint32_t)ka; a.key1 = (uint32_t)(ka >> 32); a.key2 = (uint32_t)kb;
-    const bool stochastic = (cfg->flags & SOLO_FLAG_STOCHASTIC) != 0;
-    a.xi_scale = stochastic ? 0x1p-24f : 0.0f;
-    a.xi_offset = stochastic ? (0x1p-25f - 0.5f) : 0.0f;
+    a.stochastic = (cfg->flags & SOLO_FLAG_STOCHASTIC) ? 1u : 0u;
 
     const bool has_tail = (n % solo::kTile) != 0;
     const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;

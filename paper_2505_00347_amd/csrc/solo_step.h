@@ -9,13 +9,25 @@
 // (half row), and every per-block reduction is a few DPP steps.  Nothing is
 // shared between wavefronts: there is no workgroup barrier in the kernel.
 //
-// Per iteration and lane: 128-bit loads of 8 parameters and 8 gradients, the
-// one or two code words that hold its 8+8 codes, the three block scalars;
-// unpack, dequantize, both EMAs, parameter update and 128-bit store; block
-// maxima by DPP butterflies; the quantile by a per-lane sorting network and
-// r rounds of "extract the block minimum"; the base alpha; both encoders;
-// codes OR-ed into an LDS image of the super-tile's code words, which is
-// written out with coalesced stores after the fifth iteration.
+// The kernel is bound by vector-ALU issue as much as by HBM (packed FP32 is
+// off, so a CU retires 64 lane-operations per clock: about 80 per parameter at
+// 70 % of the HBM peak).  Everything below is shaped by instruction count:
+//   * both dequantizers are table look-ups: the lanes of a group compute the
+//     block's level tables (alpha^q * Delta_v, (c-L) * Delta_m/L) once and park
+//     them in LDS; an element costs one bit-field extract, one address add and
+//     one ds_read per moment;
+//   * the p-quantile is exact: each lane sorts its 8 values with min3/med3/max3
+//     (32 instructions), parks the sorted column in LDS, and the group runs r
+//     rounds of "row minimum by DPP, the lane that holds it pops its column";
+//     a scalar population count detects the rounds in which two lanes tie and
+//     only those rounds pay for the tie-break;
+//   * the two per-block divisions share one IEEE division sequence (even lanes
+//     divide x_p by Delta_v, odd lanes L by Delta_m);
+//   * the base alpha = rho^(1/K) is found by testing G consecutive binary32
+//     candidates around a hardware exp2/log2 guess, one per lane;
+//   * codes are rounded in the float domain and accumulated with FMAs
+//     (acc = acc * 2^b + code); xi is built as a float in [1, 2) by one
+//     bit-align of the hashed word.
 //
 // Arithmetic contract (what makes the stored bytes reproducible): every value
 // that decides a code or a scale is computed in binary32, one rounding per
@@ -33,9 +45,12 @@ constexpr int kTile = 2560;        // elements per wavefront super-tile
 constexpr int kIter = 512;         // elements per iteration (64 lanes x 8)
 constexpr int kIters = kTile / kIter;
 constexpr int kWaves = 4;          // wavefronts per workgroup
+constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
+constexpr int kColPad = 160;       // slack so that a runaway column index stays inside LDS
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
 constexpr float kRhoMin = 0x1p-64f;
 constexpr uint32_t kInfBits = 0x7F800000u;
+constexpr uint32_t kOneBits = 0x3F800000u;
 
 struct StepArgs {
     float *param;
@@ -56,7 +71,7 @@ struct StepArgs {
     float quantile_p;
     uint32_t rank_full;     // rank of the quantile in a full block
     uint32_t key0, key1, key2;
-    float xi_scale, xi_offset;  // 2^-24 and 2^-25 - 0.5, or 0 and 0 (xi off)
+    uint32_t stochastic;    // 0: xi = 0
 };
 
 // ---------------------------------------------------------------- cross-lane
@@ -85,19 +100,40 @@ struct UMax { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_
 
 __device__ __forceinline__ uint32_t f2u(float x) { return __builtin_bit_cast(uint32_t, x); }
 __device__ __forceinline__ float u2f(uint32_t x) { return __builtin_bit_cast(float, x); }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+// Median of three bit patterns of non-negative floats (they order like the floats).
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return f2u(__builtin_amdgcn_fmed3f(u2f(a), u2f(b), u2f(c)));
+}
+
+// The bits of a wave-wide ballot that belong to this lane's group, shifted down.
+__device__ __forceinline__ uint32_t group_bits(uint64_t ballot, uint32_t lane, uint32_t gshift, uint32_t gmask)
+{
+    const uint32_t half = lane < 32u ? (uint32_t)ballot : (uint32_t)(ballot >> 32);
+    return (half >> gshift) & gmask;
+}
 
 __device__ __forceinline__ void cswap(uint32_t &a, uint32_t &b)
 {
-    uint32_t lo = a < b ? a : b, hi = a < b ? b : a;
+    const uint32_t lo = umin(a, b), hi = umax(a, b);
     a = lo; b = hi;
 }
 
-// Batcher's odd-even merge sort for 8 keys, 19 compare-exchanges.
+// Sorts four keys with seven instructions: a three-sort (min3, med3, max3),
+// then the fourth key is placed by one min, two med3 and one max.
+__device__ __forceinline__ void sort4(uint32_t &a, uint32_t &b, uint32_t &c, uint32_t &d)
+{
+    const uint32_t lo = umin(umin(a, b), c), mid = umed3(a, b, c), hi = umax(umax(a, b), c);
+    a = umin(lo, d); b = umed3(lo, mid, d); c = umed3(mid, hi, d); d = umax(hi, d);
+}
+
+// Eight keys: two four-sorts and Batcher's odd-even merge of the halves.
 __device__ __forceinline__ void sort8(uint32_t (&k)[8])
 {
-    cswap(k[0], k[1]); cswap(k[2], k[3]); cswap(k[4], k[5]); cswap(k[6], k[7]);
-    cswap(k[0], k[2]); cswap(k[1], k[3]); cswap(k[4], k[6]); cswap(k[5], k[7]);
-    cswap(k[1], k[2]); cswap(k[5], k[6]);
+    sort4(k[0], k[1], k[2], k[3]);
+    sort4(k[4], k[5], k[6], k[7]);
     cswap(k[0], k[4]); cswap(k[1], k[5]); cswap(k[2], k[6]); cswap(k[3], k[7]);
     cswap(k[2], k[4]); cswap(k[3], k[5]);
     cswap(k[1], k[2]); cswap(k[3], k[4]); cswap(k[5], k[6]);
@@ -113,31 +149,38 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h)
     return h;
 }
 
-// Last level alpha^K of the log codebook, K = 2^BV - 1, multiplied in the same
-// order as the dequantizer: ((a * a^2) * a^4) * a^8.
+// Level alpha^q of the log codebook for a run-time q, by binary powering in the
+// dequantizer's fixed order: the selected powers a, a^2, a^4, a^8 are
+// multiplied from the lowest bit of q up.
+template <int BV>
+__device__ __forceinline__ float log_level(uint32_t q, float P1, float P2, float P4, float P8)
+{
+    float y = (q & 1u) ? P1 : 1.0f;
+    y = (q & 2u) ? y * P2 : y;
+    if (BV >= 3) y = (q & 4u) ? y * P4 : y;
+    if (BV >= 4) y = (q & 8u) ? y * P8 : y;
+    return y;
+}
+
+// Last level alpha^K, K = 2^BV - 1: ((a * a^2) * a^4) * a^8.
 template <int BV>
 __device__ __forceinline__ float last_level(float a)
 {
-    float a2 = a * a;
+    const float a2 = a * a;
     float r = a * a2;
-    if (BV >= 3) { float a4 = a2 * a2; r = r * a4; if (BV >= 4) { float a8 = a4 * a4; r = r * a8; } }
+    if (BV >= 3) { const float a4 = a2 * a2; r = r * a4; if (BV >= 4) { const float a8 = a4 * a4; r = r * a8; } }
     return r;
 }
 
-// alpha = rho^(1/K): the largest binary32 in (0,1] whose last level does not
-// exceed rho (0 < rho < 1).  A hardware exp2/log2 guess is walked to that value
-// one ulp at a time; both walks are bounded.
+// Walks y (bits of a binary32 in (0, 1]) to the largest value whose last level
+// does not exceed rho.  Both walks are bounded; used only when the parallel
+// candidate test did not bracket the answer.
 template <int BV>
-__device__ __forceinline__ float solve_base(float rho)
+__device__ __noinline__ uint32_t walk_base(uint32_t y, float rho)
 {
-    constexpr float invK = 1.0f / (float)((1 << BV) - 1);
-    float y0 = __builtin_amdgcn_exp2f(__builtin_amdgcn_logf(rho) * invK);
-    uint32_t y = f2u(y0);
-    if (!(y <= 0x3F800000u)) y = 0x3F800000u;
-    if (y < 0x00800000u) y = 0x00800000u;
-    for (int i = 0; i < 512 && last_level<BV>(u2f(y)) > rho; ++i) --y;
-    for (int i = 0; i < 512 && y < 0x3F800000u && last_level<BV>(u2f(y + 1)) <= rho; ++i) ++y;
-    return u2f(y);
+    for (int i = 0; i < 4096 && last_level<BV>(u2f(y)) > rho; ++i) --y;
+    for (int i = 0; i < 4096 && y < kOneBits && last_level<BV>(u2f(y + 1)) <= rho; ++i) ++y;
+    return y;
 }
 
 // Eight consecutive BITS-wide codes starting at slot `slot` of word w0 (the
@@ -146,7 +189,7 @@ template <int BITS>
 __device__ __forceinline__ uint32_t extract8(uint32_t w0, uint32_t w1, uint32_t slot)
 {
     if (BITS == 3) {
-        uint64_t both = (uint64_t)w0 | ((uint64_t)w1 << 30);
+        const uint64_t both = (uint64_t)w0 | ((uint64_t)w1 << 30);
         return (uint32_t)(both >> (3u * slot)) & 0xFFFFFFu;
     }
     return w0 >> (BITS * slot);   // 2-bit: slot 0 or 8; 4-bit: slot 0
@@ -158,26 +201,34 @@ template <int BM, int BV, int B, bool BF16, bool TAIL>
 __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
 {
     constexpr int G = B / 8;                       // lanes per block
+    constexpr int NG = 64 / G;                     // blocks per iteration
     constexpr int L = (1 << (BM - 1)) - 1;
     constexpr int K = (1 << BV) - 1;
     constexpr int CM = 32 / BM, CV = 32 / BV;      // codes per word
     constexpr int MW = kTile / CM, VW = kTile / CV; // words per super-tile
     constexpr uint32_t MMASK = (1u << BM) - 1u, VMASK = (1u << BV) - 1u;
+    constexpr int VT = K + 1;                      // entries of a block's v level table
+    constexpr int MT = 2 * L + 1;                  // entries of a block's m level table
+    constexpr int MTS = 16;                        // stride of the m tables
+    constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
 
     __shared__ uint32_t lds_m[kWaves][MW + 1];     // new code words of the super-tile
     __shared__ uint32_t lds_v[kWaves][VW + 1];
-    __shared__ uint32_t lds_sort[kWaves][9 * 64];  // per-lane sorted columns + sentinel row
+    __shared__ __attribute__((aligned(16))) uint32_t lds_sort[kWaves][64 * kColStride + kColPad];
+    __shared__ float lds_tv[kWaves][NG * VT];
+    __shared__ float lds_tm[kWaves][NG * MTS];
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     const uint64_t tile = TAIL ? a.n_tiles_full : (uint64_t)blockIdx.x * kWaves + wave;
     if (!TAIL && tile >= a.n_tiles_full) return;
 
-    uint32_t *out_m = lds_m[wave], *out_v = lds_v[wave];
-    uint32_t *col = &lds_sort[wave][lane];
+    uint32_t *const out_m = lds_m[wave], *const out_v = lds_v[wave];
+    uint32_t *const col = &lds_sort[wave][lane * kColStride];
+    float *const tab_v = lds_tv[wave], *const tab_m = lds_tm[wave];
     for (uint32_t w = lane; w < MW + 1; w += 64) out_m[w] = 0;
     for (uint32_t w = lane; w < VW + 1; w += 64) out_v[w] = 0;
-    col[8 * 64] = kInfBits;
+    col[8] = kInfBits; col[9] = kInfBits; col[10] = kInfBits; col[11] = kInfBits;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -185,9 +236,11 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
     const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
     const uint64_t tile_e0 = tile * kTile;
     const uint32_t lig = lane & (G - 1);               // lane in group
-    const uint32_t gbase = lane & ~(uint32_t)(G - 1);
+    const uint32_t grp = lane / G;                     // group (block) inside the iteration
+    const uint32_t gshift = lane & 31u & ~(uint32_t)(G - 1);   // group's first lane inside its 32-lane half
     const uint32_t below = (1u << lig) - 1u;
-    const uint32_t gmask = (G == 16) ? 0xFFFFu : 0xFFu;
+    float *const my_tv = tab_v + grp * VT;
+    float *const my_tm = tab_m + grp * MTS;
 
 #pragma unroll 1
     for (int it = 0; it < kIters; ++it) {
@@ -209,7 +262,7 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
         bool ok[8];
         if (!TAIL) {
             const float4 *pp = reinterpret_cast<const float4 *>(a.param + e0);
-            float4 p0 = pp[0], p1 = pp[1];
+            const float4 p0 = pp[0], p1 = pp[1];
             p[0] = p0.x; p[1] = p0.y; p[2] = p0.z; p[3] = p0.w;
             p[4] = p1.x; p[5] = p1.y; p[6] = p1.z; p[7] = p1.w;
             if (BF16) {
@@ -220,7 +273,7 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
                 g[6] = u2f(gb.w << 16); g[7] = u2f(gb.w & 0xFFFF0000u);
             } else {
                 const float4 *gp = reinterpret_cast<const float4 *>(static_cast<const float *>(a.grad) + e0);
-                float4 g0 = gp[0], g1 = gp[1];
+                const float4 g0 = gp[0], g1 = gp[1];
                 g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w;
                 g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
             }
@@ -247,32 +300,45 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
         const uint32_t vw0 = a.v_words[gv0], vw1 = (BV == 3) ? a.v_words[gv1] : 0u;
         const float dm_old = a.m_scale[blk], dv_old = a.v_scale[blk], al_old = a.v_base[blk];
 
-        // ---- dequantize, EMA, parameter
+        // ---- level tables of this lane's block: entries lig, lig + G, ...
+        {
+            const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
+            const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
+#pragma unroll
+            for (int r = 0; r < (VT + G - 1) / G; ++r) {
+                const uint32_t q = lig + r * G;
+                if (q < VT) my_tv[q] = log_level<BV>(q, P1, P2, P4, P8) * dv_old;
+            }
+#pragma unroll
+            for (int r = 0; r < (MT + G - 1) / G; ++r) {
+                const uint32_t c = lig + r * G;
+                if (c < MT) my_tm[c] = (float)((int)c - L) * s_m;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- dequantize (table look-up), EMA, parameter
         const uint32_t mc8 = extract8<BM>(mw0, mw1, sm);
         const uint32_t vc8 = extract8<BV>(vw0, vw1, sv);
-        const float s_m = dm_old / (float)L;
-        const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
-        float mh[8], vh[8];
-        uint32_t m_absmax = 0, v_max = 0;
+        float mt[8], vt[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int cm = (int)((mc8 >> (BM * j)) & MMASK);
-            const uint32_t cv = (vc8 >> (BV * j)) & VMASK;
-            const float mt = (float)(cm - L) * s_m;
-            float y = (cv & 1u) ? P1 : 1.0f;
-            if (cv & 2u) y = y * P2;
-            if (BV >= 3) { if (cv & 4u) y = y * P4; }
-            if (BV >= 4) { if (cv & 8u) y = y * P8; }
-            const float vt = y * dv_old;
-            mh[j] = __builtin_fmaf(a.beta1, mt, a.omb1 * g[j]);
-            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (g[j] * g[j]));
+            mt[j] = my_tm[(mc8 >> (BM * j)) & MMASK];
+            vt[j] = my_tv[(vc8 >> (BV * j)) & VMASK];
+        }
+        float mh[8], vh[8];
+        float m_absmax = 0.0f, v_max = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            mh[j] = __builtin_fmaf(a.beta1, mt[j], a.omb1 * g[j]);
+            vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (g[j] * g[j]));
             // parameter: decoupled decay, bias-corrected Adam direction
             const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.inv_sqrt_bc2, a.eps);
             p[j] = __builtin_fmaf(p[j], a.decay, -(a.step_size * mh[j]) * __builtin_amdgcn_rcpf(denom));
             if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
-            const uint32_t am = f2u(mh[j]) & 0x7FFFFFFFu;
-            m_absmax = am > m_absmax ? am : m_absmax;
-            v_max = f2u(vh[j]) > v_max ? f2u(vh[j]) : v_max;
+            m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
+            v_max = __builtin_fmaxf(v_max, vh[j]);
         }
         if (!TAIL) {
             float4 *pp = reinterpret_cast<float4 *>(a.param + e0);
@@ -283,75 +349,100 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
             for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
         }
 
-        // ---- block statistics: maxima, then the r-th smallest v^
-        float dm = u2f(group_reduce<G>(m_absmax, UMax()));
-        float dv = u2f(group_reduce<G>(v_max, UMax()));
+        // ---- block maxima (non-negative floats order like their bit patterns)
+        float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
+        float dv = u2f(group_reduce<G>(f2u(v_max), UMax()));
         if (dm < kTiny) dm = 0.0f;
         if (dv < kTiny) dv = 0.0f;
 
+        // ---- the r-th smallest v^ of the block
         uint32_t key[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) key[j] = (TAIL && !ok[j]) ? kInfBits : f2u(vh[j]);
         sort8(key);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) col[j * 64] = key[j];
+        *reinterpret_cast<uint4 *>(col) = make_uint4(key[0], key[1], key[2], key[3]);
+        *reinterpret_cast<uint4 *>(col + 4) = make_uint4(key[4], key[5], key[6], key[7]);
         uint32_t r_mine = a.rank_full;
         if (TAIL) {
-            float x = __builtin_ceilf(a.quantile_p * (float)nb);
+            const float x = __builtin_ceilf(a.quantile_p * (float)nb);
             r_mine = x < 1.0f ? 1u : (uint32_t)x;
             r_mine = r_mine > nb ? nb : r_mine;
         }
-        uint32_t head = key[0], ptr = 0, xp_bits = 0;
+        uint32_t head = key[0], pidx = 0, xp_bits = 0;
         for (uint32_t k = 0; k < a.rank_full; ++k) {
             const uint32_t mn = group_reduce<G>(head, UMin());
-            const bool is_min = head == mn;
-            const uint64_t bal = __builtin_amdgcn_ballot_w64(is_min);
-            const uint32_t grp = (uint32_t)(bal >> gbase) & gmask;
-            const bool win = is_min && ((grp & below) == 0u);   // lowest lane of the group pops
-            if (k + 1 == r_mine) xp_bits = mn;
-            ptr += (win && ptr < 8u) ? 1u : 0u;   // row 8 is the +inf sentinel
-            head = col[ptr * 64];
+            bool pop = head == mn;
+            const uint64_t holders = __builtin_amdgcn_ballot_w64(pop);
+            // one holder per group is the common case; a tie costs three more instructions:
+            // only the lowest holder of a group pops, so exactly one key leaves per round
+            if (__builtin_popcountll(holders) != NG)
+                pop = pop && (group_bits(holders, lane, gshift, GMASK) & below) == 0u;
+            if (TAIL) { if (k + 1 == r_mine) xp_bits = mn; } else xp_bits = mn;
+            if (pop) {
+                pidx = TAIL ? umin(pidx + 1u, 8u) : pidx + 1u;
+                head = col[pidx];
+            }
         }
 
-        // ---- log base of the block
+        // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
+        const float num = (lane & 1u) ? (float)L : u2f(xp_bits);
+        const float den = (lane & 1u) ? dm : dv;
+        const float quo = num / den;
+        float rho = u2f(dpp<0xA0>(f2u(quo)));        // quad_perm [0,0,2,2]
+        float inv_s = u2f(dpp<0xF5>(f2u(quo)));      // quad_perm [1,1,3,3]
+        inv_s = dm > 0.0f ? inv_s : 0.0f;
+        rho = dv > 0.0f ? rho : 1.0f;
+        rho = rho < kRhoMin ? kRhoMin : rho;
+
+        // ---- alpha: largest binary32 whose last level is <= rho; one candidate per lane
         float alpha = 1.0f, inv_l2a = 0.0f, rdv = 0.0f, bias = 1.0f;
-        if (dv > 0.0f) {
-            float rho = u2f(xp_bits) / dv;
-            rho = rho < kRhoMin ? kRhoMin : rho;
-            if (rho < 1.0f) {
-                alpha = solve_base<BV>(rho);
+        {
+            constexpr float invK = 1.0f / (float)K;
+            const bool need = rho < 1.0f;
+            const float y0 = __builtin_amdgcn_exp2f(__builtin_amdgcn_logf(rho) * invK);
+            const uint32_t yb = umed3(f2u(y0), 0x00800000u, kOneBits);
+            const uint32_t cand = umin(yb + lig - (uint32_t)(G / 2), kOneBits);
+            const bool fits = last_level<BV>(u2f(cand)) <= rho;
+            const uint32_t cnt = (uint32_t)__builtin_popcount(
+                group_bits(__builtin_amdgcn_ballot_w64(fits), lane, gshift, GMASK));
+            uint32_t ab = umin(yb + cnt - 1u - (uint32_t)(G / 2), kOneBits);
+            // not bracketed (all or none of the candidates fit): walk from the nearest end
+            const bool open = need && (cnt == 0u || cnt == (uint32_t)G);
+            if (__builtin_amdgcn_ballot_w64(open) != 0) {
+                if (open) ab = walk_base<BV>(cnt == 0u ? yb - (uint32_t)(G / 2) : ab, rho);
+            }
+            if (need) {
+                alpha = u2f(ab);
                 inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(alpha));
                 rdv = __builtin_amdgcn_rcpf(dv);
                 bias = 0.0f;
             }
         }
 
-        // ---- xi: one hashed start and stride per 8 elements
+        // ---- xi: one hashed start and stride per 8 elements; 1.5 + xi - 2^-24 as a float in [1,2)
         const uint64_t gidx = (a.index_offset + e0) >> 3;
-        const uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
-        const uint32_t Y = mix32(X ^ a.key1) | 1u;
+        uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
+        uint32_t Y = mix32(X ^ a.key1) | 1u;
+        if (!a.stochastic) { X = 0x80000000u; Y = 0u; }     // xi = 0: the float is 1.5
 
-        // ---- encode and pack
-        const float inv_s = dm > 0.0f ? (float)L / dm : 0.0f;
-        uint32_t m8 = 0, v8 = 0;
+        // ---- encode: codes rounded in the float domain, four to an accumulator
+        // m: code - L = rint(m^ * L/Delta_m) in [-L, L];  v: code + 1 = floor(log_alpha(v^/Delta_v) + 1.5 + xi)
+        float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 7; j >= 0; --j) {
             float tm = __builtin_rintf(mh[j] * inv_s);
-            tm = tm > (float)L ? (float)L : tm;
-            tm = tm < -(float)L ? -(float)L : tm;
-            uint32_t cm = (uint32_t)(L + (int)tm);
-            const uint32_t u = (X + (uint32_t)j * Y) >> 8;
-            const float xi = __builtin_fmaf((float)u, a.xi_scale, a.xi_offset);
+            const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, X + (uint32_t)j * Y, 9u));
             const float ratio = __builtin_fmaf(vh[j], rdv, bias);
-            float tv = __builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, xi);
-            tv = __builtin_rintf(tv);
-            tv = tv < (float)K ? tv : (float)K;     // also catches +inf (v^ = 0) and NaN
-            tv = tv > 0.0f ? tv : 0.0f;
-            uint32_t cv = (uint32_t)tv;
-            if (TAIL && !ok[j]) { cm = 0; cv = 0; }
-            m8 |= cm << (BM * j);
-            v8 |= cv << (BV * j);
+            float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, f));
+            tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));   // +inf (v^ = 0) takes the last code
+            if (TAIL && !ok[j]) { tm = -(float)L; tv = 1.0f; }
+            if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
+            else        { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
         }
+        constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));   // L * sum 2^(BM j), j < 4
+        constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
+        const uint32_t m8 = (uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM));
+        const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
         if (BM == 3) {
             atomicOr(&out_m[wm], (m8 << (3u * sm)) & 0x3FFFFFFFu);
             atomicOr(&out_m[wm + 1], (uint32_t)(((uint64_t)m8 << (3u * sm)) >> 30));
