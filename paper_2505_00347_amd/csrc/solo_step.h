@@ -46,7 +46,7 @@ constexpr int kIter = 512;         // elements per iteration (64 lanes x 8)
 constexpr int kIters = kTile / kIter;
 constexpr int kWaves = 4;          // wavefronts per workgroup
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
-constexpr int kColPad = 160;       // slack so that a runaway column index stays inside LDS
+constexpr int kColPad = 128;       // slack so that a runaway column address stays inside LDS
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
 constexpr float kRhoMin = 0x1p-64f;
 constexpr uint32_t kInfBits = 0x7F800000u;
@@ -197,108 +197,153 @@ __device__ __forceinline__ uint32_t extract8(uint32_t w0, uint32_t w1, uint32_t 
 
 // ------------------------------------------------------------------- kernel
 
+// LDS accessed through 32-bit byte addresses, so that a table index can be
+// OR-ed into an aligned base with one v_and_or_b32.
+typedef __attribute__((address_space(3))) float lds_f32_t;
+typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+__device__ __forceinline__ float lds_f32(uint32_t addr) { return *(lds_f32_t *)(uintptr_t)addr; }
+__device__ __forceinline__ uint32_t lds_u32(uint32_t addr) { return *(lds_u32_t *)(uintptr_t)addr; }
+
+// Parameters and gradients of one lane and iteration as they come from memory.
+struct RawPG { float4 p0, p1; uint4 g0, g1; };
+
+template <bool BF16, bool TAIL>
+__device__ __forceinline__ RawPG load_pg(const StepArgs &a, uint64_t e0)
+{
+    RawPG r;
+    if (!TAIL) {
+        const float4 *pp = reinterpret_cast<const float4 *>(a.param + e0);
+        r.p0 = pp[0]; r.p1 = pp[1];
+        if (BF16) {
+            r.g0 = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.grad) + e0);
+            r.g1 = make_uint4(0, 0, 0, 0);
+        } else {
+            const uint4 *gp = reinterpret_cast<const uint4 *>(static_cast<const float *>(a.grad) + e0);
+            r.g0 = gp[0]; r.g1 = gp[1];
+        }
+    } else {                                   // element-wise, bounds-checked
+        float p[8]; uint32_t g[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = (e0 + j) < a.n;
+            p[j] = ok ? a.param[e0 + j] : 0.0f;
+            if (BF16) g[j] = ok ? (uint32_t)static_cast<const uint16_t *>(a.grad)[e0 + j] : 0u;
+            else      g[j] = ok ? static_cast<const uint32_t *>(a.grad)[e0 + j] : 0u;
+        }
+        r.p0 = make_float4(p[0], p[1], p[2], p[3]); r.p1 = make_float4(p[4], p[5], p[6], p[7]);
+        if (BF16) { r.g0 = make_uint4(g[0] | (g[1] << 16), g[2] | (g[3] << 16), g[4] | (g[5] << 16), g[6] | (g[7] << 16)); r.g1 = make_uint4(0, 0, 0, 0); }
+        else      { r.g0 = make_uint4(g[0], g[1], g[2], g[3]); r.g1 = make_uint4(g[4], g[5], g[6], g[7]); }
+    }
+    return r;
+}
+
 template <int BM, int BV, int B, bool BF16, bool TAIL>
 __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
 {
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
+    constexpr int NBT = kTile / B;                 // blocks per super-tile
     constexpr int L = (1 << (BM - 1)) - 1;
     constexpr int K = (1 << BV) - 1;
     constexpr int CM = 32 / BM, CV = 32 / BV;      // codes per word
     constexpr int MW = kTile / CM, VW = kTile / CV; // words per super-tile
-    constexpr uint32_t MMASK = (1u << BM) - 1u, VMASK = (1u << BV) - 1u;
-    constexpr int VT = K + 1;                      // entries of a block's v level table
-    constexpr int MT = 2 * L + 1;                  // entries of a block's m level table
+    constexpr int VT = K + 1;                      // entries of a block's v level table (4, 8, 16)
+    constexpr int MT = 2 * L + 1;                  // entries of a block's m level table (3, 7, 15)
     constexpr int MTS = 16;                        // stride of the m tables
     constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
+    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;   // byte-index masks
 
-    __shared__ uint32_t lds_m[kWaves][MW + 1];     // new code words of the super-tile
-    __shared__ uint32_t lds_v[kWaves][VW + 1];
+    // LDS of one wavefront: the super-tile's code words and block scalars (loaded once,
+    // updated in place, written back once), the sorted columns, the level tables.
+    __shared__ uint32_t lds_m[kWaves][MW + 4];
+    __shared__ uint32_t lds_v[kWaves][VW + 4];
+    __shared__ float lds_sc[kWaves][3 * NBT];
     __shared__ __attribute__((aligned(16))) uint32_t lds_sort[kWaves][64 * kColStride + kColPad];
-    __shared__ float lds_tv[kWaves][NG * VT];
-    __shared__ float lds_tm[kWaves][NG * MTS];
+    __shared__ __attribute__((aligned(64))) float lds_tv[kWaves][NG * VT];
+    __shared__ __attribute__((aligned(64))) float lds_tm[kWaves][NG * MTS];
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     const uint64_t tile = TAIL ? a.n_tiles_full : (uint64_t)blockIdx.x * kWaves + wave;
     if (!TAIL && tile >= a.n_tiles_full) return;
 
-    uint32_t *const out_m = lds_m[wave], *const out_v = lds_v[wave];
+    const uint64_t nblk = (a.n + B - 1) / B;
+    const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
+    const uint64_t tile_e0 = tile * kTile;
+
+    uint32_t *const img_m = lds_m[wave], *const img_v = lds_v[wave];
+    float *const sc = lds_sc[wave];
     uint32_t *const col = &lds_sort[wave][lane * kColStride];
-    float *const tab_v = lds_tv[wave], *const tab_m = lds_tm[wave];
-    for (uint32_t w = lane; w < MW + 1; w += 64) out_m[w] = 0;
-    for (uint32_t w = lane; w < VW + 1; w += 64) out_v[w] = 0;
+
+    // first parameters and gradients: in flight while the state image is staged
+    RawPG raw = load_pg<BF16, TAIL>(a, tile_e0 + lane * 8u);
+
+    // ---- stage the super-tile's state in LDS (coalesced)
+    for (uint32_t w = lane; w < MW; w += 64) {
+        const uint64_t gw = tile * MW + w;
+        uint32_t x = (!TAIL || gw < m_total) ? a.m_words[gw] : 0u;
+        if (BM == 3) x &= 0x3FFFFFFFu;
+        img_m[w] = x;
+    }
+    for (uint32_t w = lane; w < VW; w += 64) {
+        const uint64_t gw = tile * VW + w;
+        uint32_t x = (!TAIL || gw < v_total) ? a.v_words[gw] : 0u;
+        if (BV == 3) x &= 0x3FFFFFFFu;
+        img_v[w] = x;
+    }
+    if (lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
+    for (uint32_t b = lane; b < NBT; b += 64) {
+        const uint64_t gb = tile * NBT + b;
+        const bool ok = !TAIL || gb < nblk;
+        sc[b] = ok ? a.m_scale[gb] : 0.0f;
+        sc[NBT + b] = ok ? a.v_scale[gb] : 0.0f;
+        sc[2 * NBT + b] = ok ? a.v_base[gb] : 1.0f;
+    }
     col[8] = kInfBits; col[9] = kInfBits; col[10] = kInfBits; col[11] = kInfBits;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    const uint64_t nblk = (a.n + B - 1) / B;
-    const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
-    const uint64_t tile_e0 = tile * kTile;
     const uint32_t lig = lane & (G - 1);               // lane in group
     const uint32_t grp = lane / G;                     // group (block) inside the iteration
     const uint32_t gshift = lane & 31u & ~(uint32_t)(G - 1);   // group's first lane inside its 32-lane half
     const uint32_t below = (1u << lig) - 1u;
-    float *const my_tv = tab_v + grp * VT;
-    float *const my_tm = tab_m + grp * MTS;
+    float *const my_tv = lds_tv[wave] + grp * VT;
+    float *const my_tm = lds_tm[wave] + grp * MTS;
+    const uint32_t tv_addr = lds_addr(my_tv), tm_addr = lds_addr(my_tm);   // aligned to the table size
+    const uint32_t col_addr = lds_addr(col);
+    // word and slot of this lane's first code in iteration 0; an iteration advances both
+    // streams by 512 codes = (512 / C) words and (512 % C) slots
+    uint32_t wm = (lane * 8u) / CM, sm = (lane * 8u) % CM;
+    uint32_t wv = (lane * 8u) / CV, sv = (lane * 8u) % CV;
 
 #pragma unroll 1
     for (int it = 0; it < kIters; ++it) {
         const uint32_t e_loc = (uint32_t)it * kIter + lane * 8u;   // element inside the tile
         const uint64_t e0 = tile_e0 + e_loc;
-        uint64_t blk = e0 / B;
+        const uint32_t bl = (uint32_t)it * NG + grp;               // block inside the tile
         // elements of this lane's block that exist (B except in the last block)
         uint32_t nb = B;
         bool blk_ok = true;
+        bool ok[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ok[j] = !TAIL || (e0 + j) < a.n;
         if (TAIL) {
+            const uint64_t blk = tile * NBT + bl;
             blk_ok = blk < nblk;
             const uint64_t bstart = blk * B;
             nb = blk_ok ? (uint32_t)((a.n - bstart) < (uint64_t)B ? (a.n - bstart) : (uint64_t)B) : 0u;
-            if (!blk_ok) blk = nblk - 1;                   // keep the loads in bounds
         }
 
-        // ---- loads
-        float p[8], g[8];
-        bool ok[8];
-        if (!TAIL) {
-            const float4 *pp = reinterpret_cast<const float4 *>(a.param + e0);
-            const float4 p0 = pp[0], p1 = pp[1];
-            p[0] = p0.x; p[1] = p0.y; p[2] = p0.z; p[3] = p0.w;
-            p[4] = p1.x; p[5] = p1.y; p[6] = p1.z; p[7] = p1.w;
-            if (BF16) {
-                const uint4 gb = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.grad) + e0);
-                g[0] = u2f(gb.x << 16); g[1] = u2f(gb.x & 0xFFFF0000u);
-                g[2] = u2f(gb.y << 16); g[3] = u2f(gb.y & 0xFFFF0000u);
-                g[4] = u2f(gb.z << 16); g[5] = u2f(gb.z & 0xFFFF0000u);
-                g[6] = u2f(gb.w << 16); g[7] = u2f(gb.w & 0xFFFF0000u);
-            } else {
-                const float4 *gp = reinterpret_cast<const float4 *>(static_cast<const float *>(a.grad) + e0);
-                const float4 g0 = gp[0], g1 = gp[1];
-                g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w;
-                g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) ok[j] = true;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                ok[j] = (e0 + j) < a.n;
-                p[j] = ok[j] ? a.param[e0 + j] : 0.0f;
-                if (BF16) g[j] = ok[j] ? u2f((uint32_t)static_cast<const uint16_t *>(a.grad)[e0 + j] << 16) : 0.0f;
-                else      g[j] = ok[j] ? static_cast<const float *>(a.grad)[e0 + j] : 0.0f;
-            }
-        }
-        const uint32_t wm = e_loc / CM, sm = e_loc % CM;    // word and slot inside the tile
-        const uint32_t wv = e_loc / CV, sv = e_loc % CV;
-        uint64_t gm0 = tile * MW + wm, gm1 = tile * MW + (wm + 1 < MW ? wm + 1 : wm);
-        uint64_t gv0 = tile * VW + wv, gv1 = tile * VW + (wv + 1 < VW ? wv + 1 : wv);
-        if (TAIL) {
-            gm0 = gm0 < m_total ? gm0 : m_total - 1; gm1 = gm1 < m_total ? gm1 : m_total - 1;
-            gv0 = gv0 < v_total ? gv0 : v_total - 1; gv1 = gv1 < v_total ? gv1 : v_total - 1;
-        }
-        const uint32_t mw0 = a.m_words[gm0], mw1 = (BM == 3) ? a.m_words[gm1] : 0u;
-        const uint32_t vw0 = a.v_words[gv0], vw1 = (BV == 3) ? a.v_words[gv1] : 0u;
-        const float dm_old = a.m_scale[blk], dv_old = a.v_scale[blk], al_old = a.v_base[blk];
+        // ---- old state of the block and of this lane's elements (LDS)
+        const float dm_old = sc[bl], dv_old = sc[NBT + bl], al_old = sc[2 * NBT + bl];
+        const uint32_t mw0 = img_m[wm], mw1 = (BM == 3) ? img_m[wm + 1] : 0u;
+        const uint32_t vw0 = img_v[wv], vw1 = (BV == 3) ? img_v[wv + 1] : 0u;
+        const uint32_t mc8 = extract8<BM>(mw0, mw1, sm) & (uint32_t)((1ull << (8 * BM)) - 1ull);
+        const uint32_t vc8 = extract8<BV>(vw0, vw1, sv) & (uint32_t)((1ull << (8 * BV)) - 1ull);
 
         // ---- level tables of this lane's block: entries lig, lig + G, ...
         {
@@ -319,13 +364,25 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
         }
 
         // ---- dequantize (table look-up), EMA, parameter
-        const uint32_t mc8 = extract8<BM>(mw0, mw1, sm);
-        const uint32_t vc8 = extract8<BV>(vw0, vw1, sv);
+        float p[8], g[8];
+        p[0] = raw.p0.x; p[1] = raw.p0.y; p[2] = raw.p0.z; p[3] = raw.p0.w;
+        p[4] = raw.p1.x; p[5] = raw.p1.y; p[6] = raw.p1.z; p[7] = raw.p1.w;
+        if (BF16) {
+            g[0] = u2f(raw.g0.x << 16); g[1] = u2f(raw.g0.x & 0xFFFF0000u);
+            g[2] = u2f(raw.g0.y << 16); g[3] = u2f(raw.g0.y & 0xFFFF0000u);
+            g[4] = u2f(raw.g0.z << 16); g[5] = u2f(raw.g0.z & 0xFFFF0000u);
+            g[6] = u2f(raw.g0.w << 16); g[7] = u2f(raw.g0.w & 0xFFFF0000u);
+        } else {
+            g[0] = u2f(raw.g0.x); g[1] = u2f(raw.g0.y); g[2] = u2f(raw.g0.z); g[3] = u2f(raw.g0.w);
+            g[4] = u2f(raw.g1.x); g[5] = u2f(raw.g1.y); g[6] = u2f(raw.g1.z); g[7] = u2f(raw.g1.w);
+        }
         float mt[8], vt[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            mt[j] = my_tm[(mc8 >> (BM * j)) & MMASK];
-            vt[j] = my_tv[(vc8 >> (BV * j)) & VMASK];
+        for (int j = 0; j < 8; ++j) {       // byte offset 4 * code, OR-ed into the aligned table base
+            const uint32_t om = (j == 0) ? (mc8 << 2) : (mc8 >> (BM * j - 2));
+            const uint32_t ov = (j == 0) ? (vc8 << 2) : (vc8 >> (BV * j - 2));
+            mt[j] = lds_f32(tm_addr | (om & MIDX));
+            vt[j] = lds_f32(tv_addr | (ov & VIDX));
         }
         float mh[8], vh[8];
         float m_absmax = 0.0f, v_max = 0.0f;
@@ -348,6 +405,9 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
 #pragma unroll
             for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
         }
+        // next iteration's parameters and gradients: their latency hides behind the
+        // statistics, the selection and the encoders below
+        if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, e0 + kIter);
 
         // ---- block maxima (non-negative floats order like their bit patterns)
         float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
@@ -368,7 +428,7 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
             r_mine = x < 1.0f ? 1u : (uint32_t)x;
             r_mine = r_mine > nb ? nb : r_mine;
         }
-        uint32_t head = key[0], pidx = 0, xp_bits = 0;
+        uint32_t head = key[0], haddr = col_addr, xp_bits = 0;
         for (uint32_t k = 0; k < a.rank_full; ++k) {
             const uint32_t mn = group_reduce<G>(head, UMin());
             bool pop = head == mn;
@@ -379,8 +439,8 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
                 pop = pop && (group_bits(holders, lane, gshift, GMASK) & below) == 0u;
             if (TAIL) { if (k + 1 == r_mine) xp_bits = mn; } else xp_bits = mn;
             if (pop) {
-                pidx = TAIL ? umin(pidx + 1u, 8u) : pidx + 1u;
-                head = col[pidx];
+                haddr = TAIL ? umin(haddr + 4u, col_addr + 32u) : haddr + 4u;
+                head = lds_u32(haddr);
             }
         }
 
@@ -443,35 +503,49 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
         constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
         const uint32_t m8 = (uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM));
         const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
+
+        // ---- update the state image in place: XOR turns this lane's old fields into the new
+        // ones and leaves the neighbours' fields of a shared word alone
+        const uint32_t xm = mc8 ^ m8, xv = vc8 ^ v8;
         if (BM == 3) {
-            atomicOr(&out_m[wm], (m8 << (3u * sm)) & 0x3FFFFFFFu);
-            atomicOr(&out_m[wm + 1], (uint32_t)(((uint64_t)m8 << (3u * sm)) >> 30));
+            atomicXor(&img_m[wm], (xm << (3u * sm)) & 0x3FFFFFFFu);
+            atomicXor(&img_m[wm + 1], (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30));
         } else {
-            atomicOr(&out_m[wm], m8 << (BM * sm));
+            atomicXor(&img_m[wm], xm << (BM * sm));
         }
         if (BV == 3) {
-            atomicOr(&out_v[wv], (v8 << (3u * sv)) & 0x3FFFFFFFu);
-            atomicOr(&out_v[wv + 1], (uint32_t)(((uint64_t)v8 << (3u * sv)) >> 30));
+            atomicXor(&img_v[wv], (xv << (3u * sv)) & 0x3FFFFFFFu);
+            atomicXor(&img_v[wv + 1], (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30));
         } else {
-            atomicOr(&out_v[wv], v8 << (BV * sv));
+            atomicXor(&img_v[wv], xv << (BV * sv));
         }
-        if (lig == 0 && blk_ok) {
-            a.m_scale[blk] = dm;
-            a.v_scale[blk] = dv;
-            a.v_base[blk] = alpha;
-        }
+        if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
+        (void)blk_ok;
+
+        wm += kIter / CM; sm += kIter % CM;
+        if (sm >= (uint32_t)CM) { sm -= CM; wm += 1; }
+        wv += kIter / CV; sv += kIter % CV;
+        if (sv >= (uint32_t)CV) { sv -= CV; wv += 1; }
     }
 
-    // ---- write the super-tile's code words
+    // ---- write the super-tile's state back (coalesced)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     for (uint32_t w = lane; w < MW; w += 64) {
         const uint64_t gw = tile * MW + w;
-        if (!TAIL || gw < m_total) a.m_words[gw] = out_m[w];
+        if (!TAIL || gw < m_total) a.m_words[gw] = img_m[w];
     }
     for (uint32_t w = lane; w < VW; w += 64) {
         const uint64_t gw = tile * VW + w;
-        if (!TAIL || gw < v_total) a.v_words[gw] = out_v[w];
+        if (!TAIL || gw < v_total) a.v_words[gw] = img_v[w];
+    }
+    for (uint32_t b = lane; b < NBT; b += 64) {
+        const uint64_t gb = tile * NBT + b;
+        if (!TAIL || gb < nblk) {
+            a.m_scale[gb] = sc[b];
+            a.v_scale[gb] = sc[NBT + b];
+            a.v_base[gb] = sc[2 * NBT + b];
+        }
     }
 }
 
