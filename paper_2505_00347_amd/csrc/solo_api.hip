@@ -156,6 +156,7 @@ int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_
     a.v_words = v_codes; a.v_scale = v_scale; a.v_base = v_base;
     a.n = n;
     a.n_tiles_full = n / solo::kTile;
+    a.wg_per_xcd = ((a.n_tiles_full + solo::kWaves - 1) / solo::kWaves + solo::kXcds - 1) / solo::kXcds;
     a.index_offset = cfg->index_offset;
     a.beta1 = cfg->beta1; a.omb1 = 1.0f - cfg->beta1;
     a.beta2 = cfg->beta2; a.omb2 = 1.0f - cfg->beta2;

@@ -39,12 +39,17 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef SOLO_MIN_WAVES
+#define SOLO_MIN_WAVES 1   // minimum wavefronts per SIMD the register allocator must allow
+#endif
+
 namespace solo {
 
 constexpr int kTile = 2560;        // elements per wavefront super-tile
 constexpr int kIter = 512;         // elements per iteration (64 lanes x 8)
 constexpr int kIters = kTile / kIter;
 constexpr int kWaves = 4;          // wavefronts per workgroup
+constexpr int kXcds = 8;           // accelerator dies of an MI355X (each has its own L2)
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
 constexpr int kColPad = 128;       // slack so that a runaway column address stays inside LDS
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
@@ -62,6 +67,7 @@ struct StepArgs {
     float *v_base;
     uint64_t n;             // elements
     uint64_t n_tiles_full;  // super-tiles that lie entirely inside [0, n)
+    uint64_t wg_per_xcd;    // workgroups per XCD: ceil(ceil(n_tiles_full / kWaves) / 8)
     uint64_t index_offset;  // global index of element 0 (multiple of 8)
     float beta1, omb1, beta2, omb2;
     float decay;            // 1 - lr * weight_decay
@@ -208,24 +214,49 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
 __device__ __forceinline__ float lds_f32(uint32_t addr) { return *(lds_f32_t *)(uintptr_t)addr; }
 __device__ __forceinline__ uint32_t lds_u32(uint32_t addr) { return *(lds_u32_t *)(uintptr_t)addr; }
 
-// Parameters and gradients of one lane and iteration as they come from memory.
+// Streaming accesses: 128-bit, every instruction covers one contiguous kilobyte of the
+// wavefront's chunk, non-temporal (nothing of p or g is touched twice).
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load_f4(const float *p)
+{
+    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 stream_load_u4(const void *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store_f4(float *p, float4 x)
+{
+    const f32x4_t v = {x.x, x.y, x.z, x.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p));
+}
+
+// Parameters and gradients of one lane and iteration as they come from memory.  In the
+// full-tile kernel the fp32 streams arrive in the coalesced layout (lane l holds elements
+// 4l..4l+3 and 256+4l..256+4l+3 of the 512-element chunk) and are transposed through LDS
+// to the lane's 8 consecutive elements; bf16 gradients (16 bytes per lane) already are
+// both.  The tail kernel loads element by element with bounds checks.
 struct RawPG { float4 p0, p1; uint4 g0, g1; };
 
 template <bool BF16, bool TAIL>
-__device__ __forceinline__ RawPG load_pg(const StepArgs &a, uint64_t e0)
+__device__ __forceinline__ RawPG load_pg(const StepArgs &a, uint64_t chunk_e0, uint32_t lane)
 {
     RawPG r;
     if (!TAIL) {
-        const float4 *pp = reinterpret_cast<const float4 *>(a.param + e0);
-        r.p0 = pp[0]; r.p1 = pp[1];
+        const float *pp = a.param + chunk_e0 + lane * 4u;
+        r.p0 = stream_load_f4(pp); r.p1 = stream_load_f4(pp + 256);
         if (BF16) {
-            r.g0 = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.grad) + e0);
+            r.g0 = stream_load_u4(static_cast<const uint16_t *>(a.grad) + chunk_e0 + lane * 8u);
             r.g1 = make_uint4(0, 0, 0, 0);
         } else {
-            const uint4 *gp = reinterpret_cast<const uint4 *>(static_cast<const float *>(a.grad) + e0);
-            r.g0 = gp[0]; r.g1 = gp[1];
+            const float *gp = static_cast<const float *>(a.grad) + chunk_e0 + lane * 4u;
+            r.g0 = stream_load_u4(gp); r.g1 = stream_load_u4(gp + 256);
         }
     } else {                                   // element-wise, bounds-checked
+        const uint64_t e0 = chunk_e0 + lane * 8u;
         float p[8]; uint32_t g[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -241,8 +272,16 @@ __device__ __forceinline__ RawPG load_pg(const StepArgs &a, uint64_t e0)
     return r;
 }
 
+// Wave-level ordering point for LDS traffic between lanes of one wavefront (LDS executes a
+// wavefront's operations in order; this only stops the compiler from moving them).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <int BM, int BV, int B, bool BF16, bool TAIL>
-__global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
+__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const StepArgs a)
 {
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
@@ -265,10 +304,15 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
     __shared__ __attribute__((aligned(16))) uint32_t lds_sort[kWaves][64 * kColStride + kColPad];
     __shared__ __attribute__((aligned(64))) float lds_tv[kWaves][NG * VT];
     __shared__ __attribute__((aligned(64))) float lds_tm[kWaves][NG * MTS];
+    __shared__ __attribute__((aligned(16))) float4 lds_stage[kWaves][kIter / 4];   // layout transposition of p (and fp32 g)
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
-    const uint64_t tile = TAIL ? a.n_tiles_full : (uint64_t)blockIdx.x * kWaves + wave;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; workgroup (x + 8 i) takes the i-th
+    // group of super-tiles of XCD x's contiguous eighth of the buffer, so the wavefronts that
+    // run at the same time on one XCD stream through one narrow address window.
+    const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
+    const uint64_t tile = TAIL ? a.n_tiles_full : wg * kWaves + wave;
     if (!TAIL && tile >= a.n_tiles_full) return;
 
     const uint64_t nblk = (a.n + B - 1) / B;
@@ -280,7 +324,8 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
     uint32_t *const col = &lds_sort[wave][lane * kColStride];
 
     // first parameters and gradients: in flight while the state image is staged
-    RawPG raw = load_pg<BF16, TAIL>(a, tile_e0 + lane * 8u);
+    RawPG raw = load_pg<BF16, TAIL>(a, tile_e0, lane);
+    float4 *const stage = lds_stage[wave];
 
     // ---- stage the super-tile's state in LDS (coalesced)
     for (uint32_t w = lane; w < MW; w += 64) {
@@ -365,16 +410,34 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
 
         // ---- dequantize (table look-up), EMA, parameter
         float p[8], g[8];
-        p[0] = raw.p0.x; p[1] = raw.p0.y; p[2] = raw.p0.z; p[3] = raw.p0.w;
-        p[4] = raw.p1.x; p[5] = raw.p1.y; p[6] = raw.p1.z; p[7] = raw.p1.w;
-        if (BF16) {
-            g[0] = u2f(raw.g0.x << 16); g[1] = u2f(raw.g0.x & 0xFFFF0000u);
-            g[2] = u2f(raw.g0.y << 16); g[3] = u2f(raw.g0.y & 0xFFFF0000u);
-            g[4] = u2f(raw.g0.z << 16); g[5] = u2f(raw.g0.z & 0xFFFF0000u);
-            g[6] = u2f(raw.g0.w << 16); g[7] = u2f(raw.g0.w & 0xFFFF0000u);
-        } else {
-            g[0] = u2f(raw.g0.x); g[1] = u2f(raw.g0.y); g[2] = u2f(raw.g0.z); g[3] = u2f(raw.g0.w);
-            g[4] = u2f(raw.g1.x); g[5] = u2f(raw.g1.y); g[6] = u2f(raw.g1.z); g[7] = u2f(raw.g1.w);
+        {
+            float4 pa = raw.p0, pb = raw.p1;
+            uint4 ga = raw.g0, gb = raw.g1;
+            if (!TAIL) {                       // coalesced layout -> 8 consecutive elements per lane
+                stage[lane] = pa; stage[64 + lane] = pb;
+                wave_lds_sync();
+                pa = stage[2 * lane]; pb = stage[2 * lane + 1];
+                if (!BF16) {
+                    wave_lds_sync();
+                    stage[lane] = make_float4(u2f(ga.x), u2f(ga.y), u2f(ga.z), u2f(ga.w));
+                    stage[64 + lane] = make_float4(u2f(gb.x), u2f(gb.y), u2f(gb.z), u2f(gb.w));
+                    wave_lds_sync();
+                    const float4 t0 = stage[2 * lane], t1 = stage[2 * lane + 1];
+                    ga = make_uint4(f2u(t0.x), f2u(t0.y), f2u(t0.z), f2u(t0.w));
+                    gb = make_uint4(f2u(t1.x), f2u(t1.y), f2u(t1.z), f2u(t1.w));
+                }
+            }
+            p[0] = pa.x; p[1] = pa.y; p[2] = pa.z; p[3] = pa.w;
+            p[4] = pb.x; p[5] = pb.y; p[6] = pb.z; p[7] = pb.w;
+            if (BF16) {
+                g[0] = u2f(ga.x << 16); g[1] = u2f(ga.x & 0xFFFF0000u);
+                g[2] = u2f(ga.y << 16); g[3] = u2f(ga.y & 0xFFFF0000u);
+                g[4] = u2f(ga.z << 16); g[5] = u2f(ga.z & 0xFFFF0000u);
+                g[6] = u2f(ga.w << 16); g[7] = u2f(ga.w & 0xFFFF0000u);
+            } else {
+                g[0] = u2f(ga.x); g[1] = u2f(ga.y); g[2] = u2f(ga.z); g[3] = u2f(ga.w);
+                g[4] = u2f(gb.x); g[5] = u2f(gb.y); g[6] = u2f(gb.z); g[7] = u2f(gb.w);
+            }
         }
         float mt[8], vt[8];
 #pragma unroll
@@ -397,17 +460,21 @@ __global__ __launch_bounds__(kWaves * 64) void step_kernel(const StepArgs a)
             m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
             v_max = __builtin_fmaxf(v_max, vh[j]);
         }
-        if (!TAIL) {
-            float4 *pp = reinterpret_cast<float4 *>(a.param + e0);
-            pp[0] = make_float4(p[0], p[1], p[2], p[3]);
-            pp[1] = make_float4(p[4], p[5], p[6], p[7]);
+        if (!TAIL) {                           // back to the coalesced layout, streamed out
+            wave_lds_sync();
+            stage[2 * lane] = make_float4(p[0], p[1], p[2], p[3]);
+            stage[2 * lane + 1] = make_float4(p[4], p[5], p[6], p[7]);
+            wave_lds_sync();
+            float *pp = a.param + (tile_e0 + (uint32_t)it * kIter) + lane * 4u;
+            stream_store_f4(pp, stage[lane]);
+            stream_store_f4(pp + 256, stage[64 + lane]);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
         }
         // next iteration's parameters and gradients: their latency hides behind the
         // statistics, the selection and the encoders below
-        if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, e0 + kIter);
+        if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
 
         // ---- block maxima (non-negative floats order like their bit patterns)
         float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
@@ -559,7 +626,7 @@ template <int BM, int BV, int B, bool BF16>
 hipError_t launch_one(const StepArgs &args, bool has_tail, hipStream_t stream)
 {
     if (args.n_tiles_full) {
-        const uint64_t grid = (args.n_tiles_full + kWaves - 1) / kWaves;
+        const uint64_t grid = args.wg_per_xcd * kXcds;
         hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, false>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
