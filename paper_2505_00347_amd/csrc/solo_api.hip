@@ -164,9 +164,16 @@ int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_
     const double bc1 = 1.0 - pow((double)cfg->beta1, (double)step);
     const double bc2 = 1.0 - pow((double)cfg->beta2, (double)step);
     a.decay = (float)(1.0 - (double)cfg->lr * (double)cfg->weight_decay);
-    a.step_size = (float)((double)cfg->lr / bc1);
-    a.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
-    a.eps = cfg->eps;
+    // p <- p * decay - m^ / (sqrt(v^) * denom_scale + denom_eps): the step size lr / bc1 is folded
+    // into the denominator; a step size too small to divide by (|.| < 2^-100) means no update
+    const double step_size = (double)cfg->lr / bc1;
+    if (fabs(step_size) < 0x1p-100) {
+        a.denom_scale = 0.0f;
+        a.denom_eps = INFINITY;
+    } else {
+        a.denom_scale = (float)(1.0 / sqrt(bc2) / step_size);
+        a.denom_eps = (float)((double)cfg->eps / step_size);
+    }
     a.quantile_p = cfg->quantile_p;
     // r = max(1, ceil(p * B)) with the product in binary32
     float x = ceilf(cfg->quantile_p * (float)cfg->block_size);

@@ -40,7 +40,7 @@
 #include <stdint.h>
 
 #ifndef SOLO_MIN_WAVES
-#define SOLO_MIN_WAVES 1   // minimum wavefronts per SIMD the register allocator must allow
+#define SOLO_MIN_WAVES 5   // wavefronts per SIMD the register allocator must leave room for
 #endif
 
 namespace solo {
@@ -48,10 +48,12 @@ namespace solo {
 constexpr int kTile = 2560;        // elements per wavefront super-tile
 constexpr int kIter = 512;         // elements per iteration (64 lanes x 8)
 constexpr int kIters = kTile / kIter;
-constexpr int kWaves = 4;          // wavefronts per workgroup
+#ifndef SOLO_WAVES
+#define SOLO_WAVES 4
+#endif
+constexpr int kWaves = SOLO_WAVES; // wavefronts per workgroup
 constexpr int kXcds = 8;           // accelerator dies of an MI355X (each has its own L2)
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
-constexpr int kColPad = 128;       // slack so that a runaway column address stays inside LDS
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
 constexpr float kRhoMin = 0x1p-64f;
 constexpr uint32_t kInfBits = 0x7F800000u;
@@ -71,9 +73,8 @@ struct StepArgs {
     uint64_t index_offset;  // global index of element 0 (multiple of 8)
     float beta1, omb1, beta2, omb2;
     float decay;            // 1 - lr * weight_decay
-    float step_size;        // lr / (1 - beta1^t)
-    float inv_sqrt_bc2;     // 1 / sqrt(1 - beta2^t)
-    float eps;
+    float denom_scale;      // (1 / sqrt(1 - beta2^t)) / step_size, step_size = lr / (1 - beta1^t)
+    float denom_eps;        // eps / step_size  (lr == 0: scale 0 and eps +inf, the update vanishes)
     float quantile_p;
     uint32_t rank_full;     // rank of the quantile in a full block
     uint32_t key0, key1, key2;
@@ -296,15 +297,23 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
     constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;   // byte-index masks
 
-    // LDS of one wavefront: the super-tile's code words and block scalars (loaded once,
-    // updated in place, written back once), the sorted columns, the level tables.
-    __shared__ uint32_t lds_m[kWaves][MW + 4];
-    __shared__ uint32_t lds_v[kWaves][VW + 4];
-    __shared__ float lds_sc[kWaves][3 * NBT];
-    __shared__ __attribute__((aligned(16))) uint32_t lds_sort[kWaves][64 * kColStride + kColPad];
-    __shared__ __attribute__((aligned(64))) float lds_tv[kWaves][NG * VT];
-    __shared__ __attribute__((aligned(64))) float lds_tm[kWaves][NG * MTS];
-    __shared__ __attribute__((aligned(16))) float4 lds_stage[kWaves][kIter / 4];   // layout transposition of p (and fp32 g)
+    // LDS of one wavefront, one contiguous slab (all offsets are compile-time constants, so the
+    // sub-arrays are reached with instruction offsets from very few address registers):
+    //   columns   64 x 12 words  per-lane sorted keys + sentinel; doubles as the staging area of
+    //                            the layout transposition at the start of an iteration
+    //   img_m/v   the super-tile's code words (loaded once, updated in place, written back once)
+    //   sc        3 x NBT block scalars (Delta_m, Delta_v, alpha), same life cycle
+    //   tv, tm    level tables of the NG blocks of the current iteration
+    // A runaway column address (possible only with non-finite input) stays inside the slab.
+    constexpr int kOffCol = 0;
+    constexpr int kOffImgM = 64 * kColStride;
+    constexpr int kOffImgV = kOffImgM + ((MW + 4 + 3) / 4) * 4;
+    constexpr int kOffTv = ((kOffImgV + VW + 4 + 15) / 16) * 16;      // 64-byte aligned
+    constexpr int kOffTm = kOffTv + ((NG * VT + 15) / 16) * 16;
+    constexpr int kOffSc = kOffTm + NG * MTS;
+    constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16;
+    static_assert(kSlab >= 64 * kColStride + 136, "column slack");
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * kSlab];
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
@@ -319,13 +328,19 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
     const uint64_t tile_e0 = tile * kTile;
 
-    uint32_t *const img_m = lds_m[wave], *const img_v = lds_v[wave];
-    float *const sc = lds_sc[wave];
-    uint32_t *const col = &lds_sort[wave][lane * kColStride];
+    uint32_t *const slab = lds_slab + wave * kSlab;
+    uint32_t *const img_m = slab + kOffImgM, *const img_v = slab + kOffImgV;
+    float *const sc = reinterpret_cast<float *>(slab + kOffSc);
+    uint32_t *const col = slab + kOffCol + lane * kColStride;
 
     // first parameters and gradients: in flight while the state image is staged
     RawPG raw = load_pg<BF16, TAIL>(a, tile_e0, lane);
-    float4 *const stage = lds_stage[wave];
+    // one pad vector after every 8 keeps both the coalesced (index = lane) and the per-lane
+    // (index = 2 lane, 2 lane + 1) accesses of the transposition free of bank conflicts
+    static_assert((kIter / 4 + kIter / 32) * 4 <= 64 * kColStride, "staging must fit the column area");
+    float4 *const stage = reinterpret_cast<float4 *>(slab + kOffCol);
+    float4 *const st_c = stage + (lane + lane / 8u);        // coalesced slots: st_c[0] and st_c[72] (= slot 64 + lane)
+    float4 *const st_l = stage + (2u * lane + lane / 4u);   // this lane's 8 elements: st_l[0], st_l[1]
 
     // ---- stage the super-tile's state in LDS (coalesced)
     for (uint32_t w = lane; w < MW; w += 64) {
@@ -348,7 +363,6 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
         sc[NBT + b] = ok ? a.v_scale[gb] : 0.0f;
         sc[2 * NBT + b] = ok ? a.v_base[gb] : 1.0f;
     }
-    col[8] = kInfBits; col[9] = kInfBits; col[10] = kInfBits; col[11] = kInfBits;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -356,8 +370,8 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     const uint32_t grp = lane / G;                     // group (block) inside the iteration
     const uint32_t gshift = lane & 31u & ~(uint32_t)(G - 1);   // group's first lane inside its 32-lane half
     const uint32_t below = (1u << lig) - 1u;
-    float *const my_tv = lds_tv[wave] + grp * VT;
-    float *const my_tm = lds_tm[wave] + grp * MTS;
+    float *const my_tv = reinterpret_cast<float *>(slab + kOffTv) + grp * VT;
+    float *const my_tm = reinterpret_cast<float *>(slab + kOffTm) + grp * MTS;
     const uint32_t tv_addr = lds_addr(my_tv), tm_addr = lds_addr(my_tm);   // aligned to the table size
     const uint32_t col_addr = lds_addr(col);
     // word and slot of this lane's first code in iteration 0; an iteration advances both
@@ -414,15 +428,15 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
             float4 pa = raw.p0, pb = raw.p1;
             uint4 ga = raw.g0, gb = raw.g1;
             if (!TAIL) {                       // coalesced layout -> 8 consecutive elements per lane
-                stage[lane] = pa; stage[64 + lane] = pb;
+                st_c[0] = pa; st_c[72] = pb;
                 wave_lds_sync();
-                pa = stage[2 * lane]; pb = stage[2 * lane + 1];
+                pa = st_l[0]; pb = st_l[1];
                 if (!BF16) {
                     wave_lds_sync();
-                    stage[lane] = make_float4(u2f(ga.x), u2f(ga.y), u2f(ga.z), u2f(ga.w));
-                    stage[64 + lane] = make_float4(u2f(gb.x), u2f(gb.y), u2f(gb.z), u2f(gb.w));
+                    st_c[0] = make_float4(u2f(ga.x), u2f(ga.y), u2f(ga.z), u2f(ga.w));
+                    st_c[72] = make_float4(u2f(gb.x), u2f(gb.y), u2f(gb.z), u2f(gb.w));
                     wave_lds_sync();
-                    const float4 t0 = stage[2 * lane], t1 = stage[2 * lane + 1];
+                    const float4 t0 = st_l[0], t1 = st_l[1];
                     ga = make_uint4(f2u(t0.x), f2u(t0.y), f2u(t0.z), f2u(t0.w));
                     gb = make_uint4(f2u(t1.x), f2u(t1.y), f2u(t1.z), f2u(t1.w));
                 }
@@ -439,6 +453,8 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
                 g[4] = u2f(gb.x); g[5] = u2f(gb.y); g[6] = u2f(gb.z); g[7] = u2f(gb.w);
             }
         }
+        // next iteration's parameters and gradients, a whole iteration ahead of their use
+        if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
         float mt[8], vt[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {       // byte offset 4 * code, OR-ed into the aligned table base
@@ -454,27 +470,25 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
             mh[j] = __builtin_fmaf(a.beta1, mt[j], a.omb1 * g[j]);
             vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (g[j] * g[j]));
             // parameter: decoupled decay, bias-corrected Adam direction
-            const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.inv_sqrt_bc2, a.eps);
-            p[j] = __builtin_fmaf(p[j], a.decay, -(a.step_size * mh[j]) * __builtin_amdgcn_rcpf(denom));
+            // p <- p * decay - step_size * m^ / (sqrt(v^ / bc2) + eps), with step_size folded into the denominator
+            const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
+            p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
             if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
             m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
             v_max = __builtin_fmaxf(v_max, vh[j]);
         }
         if (!TAIL) {                           // back to the coalesced layout, streamed out
             wave_lds_sync();
-            stage[2 * lane] = make_float4(p[0], p[1], p[2], p[3]);
-            stage[2 * lane + 1] = make_float4(p[4], p[5], p[6], p[7]);
+            st_l[0] = make_float4(p[0], p[1], p[2], p[3]);
+            st_l[1] = make_float4(p[4], p[5], p[6], p[7]);
             wave_lds_sync();
             float *pp = a.param + (tile_e0 + (uint32_t)it * kIter) + lane * 4u;
-            stream_store_f4(pp, stage[lane]);
-            stream_store_f4(pp + 256, stage[64 + lane]);
+            stream_store_f4(pp, st_c[0]);
+            stream_store_f4(pp + 256, st_c[72]);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
         }
-        // next iteration's parameters and gradients: their latency hides behind the
-        // statistics, the selection and the encoders below
-        if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
 
         // ---- block maxima (non-negative floats order like their bit patterns)
         float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
@@ -487,6 +501,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 #pragma unroll
         for (int j = 0; j < 8; ++j) key[j] = (TAIL && !ok[j]) ? kInfBits : f2u(vh[j]);
         sort8(key);
+        col[8] = kInfBits;                      // sentinel behind the lane's 8 keys (the staging overwrote it)
         *reinterpret_cast<uint4 *>(col) = make_uint4(key[0], key[1], key[2], key[3]);
         *reinterpret_cast<uint4 *>(col + 4) = make_uint4(key[4], key[5], key[6], key[7]);
         uint32_t r_mine = a.rank_full;
@@ -496,7 +511,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
             r_mine = r_mine > nb ? nb : r_mine;
         }
         uint32_t head = key[0], haddr = col_addr, xp_bits = 0;
-        for (uint32_t k = 0; k < a.rank_full; ++k) {
+        auto extract_round = [&](uint32_t k) {
             const uint32_t mn = group_reduce<G>(head, UMin());
             bool pop = head == mn;
             const uint64_t holders = __builtin_amdgcn_ballot_w64(pop);
@@ -509,7 +524,8 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
                 haddr = TAIL ? umin(haddr + 4u, col_addr + 32u) : haddr + 4u;
                 head = lds_u32(haddr);
             }
-        }
+        };
+        for (uint32_t k = 0; k < a.rank_full; ++k) extract_round(k);
 
         // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
         const float num = (lane & 1u) ? (float)L : u2f(xp_bits);
