@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X: 8 TB/s HBM3E
 
+# HBM bytes per launch of the step kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the same counter reads for a plain copy of known size (see profiles/).
+MEASURED_TRAFFIC = {}
+
 
 def bytes_per_param(w):
     """Algorithmic HBM bytes per parameter and step: read p, g, both code streams and three
@@ -100,6 +104,29 @@ def cpu_baseline(w, sample, steps=3):
                       "so the rate carries over to the full tensor set"}
 
 
+def stream_probe(n):
+    """Runs the stand-alone memory-ceiling probe (paper_2505_00347_amd/csrc/stream_probe.hip) as a
+    child process before this process touches the GPU, and returns its GB/s figures: what HBM
+    delivers on this machine for pure reads, pure writes, a copy and the step's own access pattern
+    without arithmetic.  None if the probe is not built."""
+    import re
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2505_00347_amd", "lib", "stream_probe")
+    if not os.path.exists(exe):
+        return None
+    try:
+        out = subprocess.run([exe, str(n)], capture_output=True, text=True, timeout=120).stdout
+    except Exception:
+        return None
+    res = {}
+    for key, label in (("read_gbs", "read only"), ("write_gbs", "write only"), ("copy_gbs", "copy"),
+                       ("step_shaped_gbs", "step-shaped")):
+        m = re.search(re.escape(label) + r".*?([0-9.]+) GB/s", out)
+        if m:
+            res[key] = float(m.group(1))
+    return res or None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +135,8 @@ def main():
     ap.add_argument("--workload", default="c5_llama7b_2bit_3bit")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stream-probe", action="store_true",
+                    help="skip the memory-ceiling probe (read / write / copy / step-shaped streams)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps, copy the parameter buffer once (a plain copy of "
                          "known size that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -116,9 +145,10 @@ def main():
         sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
                  "multi-GPU path (run with --gpus 1)")
 
-    import torch
     from paper_2505_00347_amd import solo, synth
+    probe = None if args.no_stream_probe else stream_probe(synth.workload(args.workload).n)
 
+    import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     solo.lib()
@@ -171,8 +201,9 @@ def main():
                    "block_size": w.block_size, "grad_dtype": w.grad_dtype, "beta1": w.beta1,
                    "bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
+                     "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3,
+                     "stream_probe": probe},
     }
     del grads, p, state
     torch.cuda.empty_cache()

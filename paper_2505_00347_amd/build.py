@@ -14,6 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libsolo.so")
+PROBE = os.path.join(LIBDIR, "stream_probe")
 SOURCES = ["solo_api.hip", "solo_step_m2.hip", "solo_step_m3.hip", "solo_step_m4.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off and IEEE divide/sqrt: the stored codes and scales depend on the exact
@@ -41,6 +42,11 @@ def build(force=True, verbose=False):
     with ThreadPoolExecutor(len(SOURCES)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    # stand-alone memory-ceiling probe (read / write / copy / step-shaped streams)
+    subprocess.check_call([HIPCC, "-O3", "--offload-arch=gfx950", "-std=c++17",
+                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                           "-Wno-unknown-warning-option",
+                           os.path.join(CSRC, "stream_probe.hip"), "-o", PROBE])
     if verbose:
         print("built", LIB)
     return LIB
