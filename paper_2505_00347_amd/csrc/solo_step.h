@@ -316,7 +316,9 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * kSlab];
 
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = threadIdx.x >> 6;
+    // the wavefront index is uniform: keeping it (and every address derived from the tile) in
+    // scalar registers frees vector registers
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     // Workgroup ids are dealt round-robin to the 8 XCDs; workgroup (x + 8 i) takes the i-th
     // group of super-tiles of XCD x's contiguous eighth of the buffer, so the wavefronts that
     // run at the same time on one XCD stream through one narrow address window.
