@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X: 8 TB/s HBM3E
 
 # HBM bytes per launch of the step kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a plain copy of known size (see profiles/).
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {"c5_llama7b_2bit_3bit": 77.407e9}   # profiles/step_kernel_c5_llama7b_traffic.txt
 
 
 def bytes_per_param(w):
@@ -184,10 +184,10 @@ def main():
     avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     assert bool(torch.isfinite(p[:1 << 20]).all())
     if args.copy_probe:
-        probe = torch.empty_like(p)
-        probe.copy_(p)                           # reads 4n bytes, writes 4n bytes
+        p_copy = torch.empty_like(p)
+        p_copy.copy_(p)                          # reads 4n bytes, writes 4n bytes
         torch.cuda.synchronize()
-        del probe
+        del p_copy
 
     ms_per_step = wall / args.steps * 1e3
     bpp = bytes_per_param(w)
