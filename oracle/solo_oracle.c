@@ -54,6 +54,8 @@ typedef struct so_config {
     float quantile_p;     /* p of the p-quantile that sets the log base        */
     uint64_t seed;        /* key of the xi stream                              */
     uint64_t index_offset;/* global index of element 0 (multiple of 8)         */
+    uint32_t m_codebook;  /* 1st-moment levels: 0 signed linear, 1 signed dynamic exponent */
+    uint32_t pad_;
 } so_config;
 
 #define SO_MAX_BLOCK 4096
@@ -107,6 +109,86 @@ float so_log_level(float alpha, uint32_t code, uint32_t bits)
 float so_dequant_v(uint32_t code, float scale, float alpha, uint32_t bits)
 {
     return so_log_level(alpha, code, bits) * scale;
+}
+
+/* ------------------------------------------------- dynamic exponent levels */
+
+/* Dynamic exponent (DE) levels (App. A): b bits = E leading zero bits that give the
+ * exponent 10^-E, one indicator bit, and the remaining bits as a linear fraction over
+ * [0.1, 1]; the signed variant spends the first bit on the sign.  With nsb = b - 1 bits after
+ * the first one and exponents 0..nsb-1, exponent step i (scale 10^(-(nsb-1)+i)) owns
+ * 2^i fraction cells (signed; 2^(i+1) unsigned), a cell is represented by the mean of its two
+ * boundaries on the grid linspace(0.1, 1, cells+1), and the codes left over are the levels 0
+ * and 1.  The result has 2^b levels, is not symmetric (+1 exists, -1 does not), and reproduces
+ * every radius of Fact A.1 for 2..8 bits.  Writes the levels in increasing order, returns
+ * their number. */
+int so_de_levels(uint32_t bits, int is_signed, double *out)
+{
+    const int nsb = (int)bits - 1;
+    int n = 0;
+    for (int i = 0; i < nsb; ++i) {
+        const int cells = is_signed ? (1 << i) : (1 << (i + 1));
+        const double scale = pow(10.0, (double)(-(nsb - 1) + i));
+        for (int c = 0; c < cells; ++c) {
+            const double lo = 0.1 + 0.9 * (double)c / (double)cells;
+            const double hi = 0.1 + 0.9 * (double)(c + 1) / (double)cells;
+            out[n++] = scale * (lo + hi) / 2.0;
+            if (is_signed) out[n++] = -scale * (lo + hi) / 2.0;
+        }
+    }
+    out[n++] = 0.0;
+    out[n++] = 1.0;
+    for (int i = 1; i < n; ++i) {                 /* insertion sort, n <= 256 */
+        double v = out[i]; int j = i - 1;
+        while (j >= 0 && out[j] > v) { out[j + 1] = out[j]; --j; }
+        out[j + 1] = v;
+    }
+    return n;
+}
+
+/* Signed DE level of a code (codes in increasing level order; code L = 2^(b-1)-1 is 0). */
+double so_de_signed_level(uint32_t code, uint32_t bits)
+{
+    double lv[256];
+    so_de_levels(bits, 1, lv);
+    return lv[code];
+}
+
+/* Q-dagger with the signed DE levels: m~ = fl(fl(y_q) * Delta). */
+float so_dequant_m_de(uint32_t code, float scale, uint32_t bits)
+{
+    return (float)so_de_signed_level(code, bits) * scale;
+}
+
+/* Eq. 1 with the signed DE levels, Delta = max|x| over the block.  The nearest level is found
+ * on the magnitude: with the non-negative levels P_0 = 0 < P_1 < ... and their midpoints
+ * M_j = fl((P_j + P_{j+1}) / 2), j = #{ j : |x * fl(1/Delta)| > M_j }, and the code is
+ * L + j for x >= 0 and L - min(j, L) for x < 0 (the negative side has no level -1).  A value
+ * exactly on a midpoint takes the level of smaller magnitude. */
+void so_quant_m_de_block(const float *x, uint32_t nb, uint32_t bits, uint16_t *codes, float *scale)
+{
+    const int L = so_L(bits);
+    double lv[256];
+    so_de_levels(bits, 1, lv);
+    float mid[128];
+    for (int j = 0; j <= L; ++j) mid[j] = (float)((lv[L + j] + lv[L + j + 1]) / 2.0);
+    float d = 0.0f;
+    for (uint32_t i = 0; i < nb; ++i) d = fmaxf(d, fabsf(x[i]));
+    if (d < SO_TINY) {
+        for (uint32_t i = 0; i < nb; ++i) codes[i] = (uint16_t)L;
+        *scale = 0.0f;
+        return;
+    }
+    const float inv = 1.0f / d;
+    for (uint32_t i = 0; i < nb; ++i) {
+        const float z = x[i] * inv;
+        const float a = fabsf(z);
+        int j = 0;
+        for (int k = 0; k <= L; ++k) j += (a > mid[k]) ? 1 : 0;
+        if (z < 0.0f) codes[i] = (uint16_t)(L - (j < L ? j : L));
+        else          codes[i] = (uint16_t)(L + j);
+    }
+    *scale = d;
 }
 
 /* ------------------------------------------------------------- random xi */
@@ -306,6 +388,7 @@ int so_step_unpacked(float *param, const float *grad,
     const uint32_t B = cfg->block_size;
     if (B == 0 || B > SO_MAX_BLOCK || step == 0) return -1;
     if (cfg->bits_m < 2 || cfg->bits_m > 16 || cfg->bits_v < 2 || cfg->bits_v > 16) return -1;
+    if (cfg->m_codebook > 1 || (cfg->m_codebook == 1 && cfg->bits_m > 8)) return -1;
     const uint64_t nblk = (n + B - 1) / B;
     const float beta1 = cfg->beta1, beta2 = cfg->beta2;
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
@@ -328,7 +411,8 @@ int so_step_unpacked(float *param, const float *grad,
         for (uint32_t k = 0; k < nb; ++k) {
             const uint64_t i = i0 + k;
             const float g = grad[i];
-            const float mt = so_dequant_m(m_codes[i], m_scale[blk], cfg->bits_m);
+            const float mt = cfg->m_codebook ? so_dequant_m_de(m_codes[i], m_scale[blk], cfg->bits_m)
+                                             : so_dequant_m(m_codes[i], m_scale[blk], cfg->bits_m);
             const float vt = so_dequant_v(v_codes[i], v_scale[blk], v_base[blk], cfg->bits_v);
             /* EMA (Sec. 3.1): the signal term is rounded, then one fused
              * multiply-add joins it to beta * state. */
@@ -340,7 +424,8 @@ int so_step_unpacked(float *param, const float *grad,
             if (mhat_out) mhat_out[i] = mh[k];
             if (vhat_out) vhat_out[i] = vh[k];
         }
-        so_quant_m_block(mh, nb, cfg->bits_m, m_codes + i0, m_scale + blk);
+        if (cfg->m_codebook) so_quant_m_de_block(mh, nb, cfg->bits_m, m_codes + i0, m_scale + blk);
+        else so_quant_m_block(mh, nb, cfg->bits_m, m_codes + i0, m_scale + blk);
         so_quant_v_block(vh, nb, cfg->bits_v, cfg->quantile_p, cfg->stochastic, keys,
                          cfg->index_offset + i0, v_codes + i0, v_scale + blk, v_base + blk,
                          margin ? margin + i0 : NULL);

@@ -35,14 +35,15 @@ class Config(C.Structure):
                 ("stochastic", C.c_uint32),
                 ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float), ("weight_decay", C.c_float), ("quantile_p", C.c_float),
-                ("seed", C.c_uint64), ("index_offset", C.c_uint64)]
+                ("seed", C.c_uint64), ("index_offset", C.c_uint64),
+                ("m_codebook", C.c_uint32), ("pad_", C.c_uint32)]
 
 
 def make_config(bits_m=4, bits_v=4, block_size=128, stochastic=1, lr=1e-3, beta1=0.8,
                 beta2=0.999, eps=1e-8, weight_decay=0.01, quantile_p=0.1, seed=42,
-                index_offset=0):
+                index_offset=0, m_codebook=0):
     return Config(bits_m, bits_v, block_size, stochastic, lr, beta1, beta2, eps,
-                  weight_decay, quantile_p, seed, index_offset)
+                  weight_decay, quantile_p, seed, index_offset, m_codebook, 0)
 
 
 _lib = None
@@ -69,6 +70,12 @@ def _declare(L):
     L.so_log_level.restype = C.c_float; L.so_log_level.argtypes = [C.c_float, C.c_uint32, C.c_uint32]
     L.so_dequant_v.restype = C.c_float
     L.so_dequant_v.argtypes = [C.c_uint32, C.c_float, C.c_float, C.c_uint32]
+    L.so_de_levels.restype = C.c_int
+    L.so_de_levels.argtypes = [C.c_uint32, C.c_int, np.ctypeslib.ndpointer(np.float64, flags="C_CONTIGUOUS")]
+    L.so_de_signed_level.restype = C.c_double; L.so_de_signed_level.argtypes = [C.c_uint32, C.c_uint32]
+    L.so_dequant_m_de.restype = C.c_float; L.so_dequant_m_de.argtypes = [C.c_uint32, C.c_float, C.c_uint32]
+    L.so_quant_m_de_block.restype = None
+    L.so_quant_m_de_block.argtypes = [_f32p, C.c_uint32, C.c_uint32, _u16p, C.POINTER(C.c_float)]
     L.so_xi_keys.restype = None; L.so_xi_keys.argtypes = [C.c_uint64, C.c_uint64, _u32p]
     L.so_xi_bits.restype = C.c_uint32; L.so_xi_bits.argtypes = [_u32p, C.c_uint64]
     L.so_xi.restype = C.c_float; L.so_xi.argtypes = [_u32p, C.c_uint64]
@@ -139,6 +146,23 @@ def xi_array(seed, step, i0, count):
 
 
 # ------------------------------------------------------------- block helpers
+
+def de_levels(bits, signed=True):
+    out = np.zeros(256, np.float64)
+    n = lib().so_de_levels(bits, 1 if signed else 0, out)
+    return out[:n].copy()
+
+
+def dequant_m_de(code, scale, bits): return np.float32(lib().so_dequant_m_de(code, scale, bits))
+
+
+def quant_m_de_block(x, bits):
+    x = np.ascontiguousarray(x, np.float32)
+    codes = np.zeros(x.size, np.uint16)
+    scale = C.c_float()
+    lib().so_quant_m_de_block(x, x.size, bits, codes, C.byref(scale))
+    return codes, np.float32(scale.value)
+
 
 def quant_m_block(x, bits):
     x = np.ascontiguousarray(x, np.float32)

@@ -327,3 +327,58 @@ def test_state_init_is_the_zero_state(so):
     st = so.State(130, so.make_config(bits_m=2, bits_v=3, block_size=64))
     assert st.m_scale.size == 3 and st.m_words.size == 9 and st.v_words.size == 13
     assert st.m_words[-1] == 0x5                                  # two codes, rest zero
+
+
+# ------------------------------------------------- dynamic exponent codebook
+
+def test_de_levels_reproduce_every_radius_of_the_paper(so):
+    """Fact A.1, DE rows: min / median / max radius for 2..8 bits, signed and unsigned."""
+    for kind, bits, rmin, rmed, rmax in read_golden("de_radii.txt"):
+        lv = so.de_levels(int(bits), kind == "signed")
+        assert lv.size == 2 ** int(bits) and np.all(np.diff(lv) > 0)
+        assert lv[-1] == 1.0 and 0.0 in lv
+        r = np.diff(lv) / 2
+        for got, want in ((r.min(), rmin), (np.median(r), rmed), (r.max(), rmax)):
+            if want != "-":
+                assert abs(got - float(want)) < 5.1e-4, (kind, bits, got, want)
+    # the signed sets used by the optimizer (sign bit + one cell per exponent step, plus 0 and 1)
+    assert np.allclose(so.de_levels(2), [-0.55, 0, 0.55, 1.0])
+    assert np.allclose(so.de_levels(3), [-0.775, -0.325, -0.055, 0, 0.055, 0.325, 0.775, 1.0])
+    assert so.de_levels(4)[7] == 0.0 and np.isclose(so.de_levels(4)[8], 0.0055)
+
+
+def test_de_swamping_thresholds_match_paper(so):
+    """beta >= 1 - r_median/2 for the signed DE sets (App. B)."""
+    for bits, beta in read_golden("swamping_thresholds_signed_de.txt"):
+        r = np.diff(so.de_levels(int(bits))) / 2
+        assert abs((1 - np.median(r) / 2) - float(beta)) < 1.1e-3
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_de_quantizer_is_nearest_level(so, bits):
+    """Eq. 1 with the DE levels: brute-force argmin over the level table in binary64."""
+    rng = np.random.default_rng(300 + bits)
+    L = 2 ** (bits - 1) - 1
+    levels = so.de_levels(bits)
+    for trial in range(40):
+        nb = int(rng.integers(1, 200))
+        x = (rng.standard_normal(nb) * 10.0 ** rng.uniform(-6, 2)).astype(np.float32)
+        if trial % 5 == 0:
+            x *= rng.random(nb).astype(np.float32) ** 8          # many values near zero
+        codes, scale = so.quant_m_de_block(x, bits)
+        assert scale == np.max(np.abs(x))
+        z = x.astype(np.float64) / float(scale)
+        dist = np.abs(z[:, None] - levels[None, :])
+        brute = np.argmin(dist, axis=1)
+        srt = np.sort(dist, axis=1)
+        clear = (srt[:, 1] - srt[:, 0]) > 1e-6 * np.maximum(np.abs(z), 1e-3)
+        assert np.array_equal(codes[clear], brute[clear])
+        assert np.all(np.abs(codes.astype(int) - brute) <= 1)
+        back = np.array([so.dequant_m_de(int(c), scale, bits) for c in codes], np.float64)
+        assert np.allclose(back, levels[codes] * float(scale), rtol=1e-6)
+        assert codes[np.argmax(np.abs(x))] == (2 * L + 1 if x[np.argmax(np.abs(x))] > 0 else 0)
+    # the zero level is code L; midpoints go to the smaller magnitude
+    assert so.dequant_m_de(L, 3.0, bits) == 0.0
+    mid = np.float32((levels[L + 1] + levels[L + 2]) / 2)
+    codes, _ = so.quant_m_de_block(np.array([1.0, mid, -mid, np.nextafter(mid, np.float32(2))], np.float32), bits)
+    assert list(codes) == [2 * L + 1, L + 1, L - 1, L + 2]

@@ -14,6 +14,13 @@ from conftest import read_golden
 
 BITS = (2, 3, 4)
 
+# Signed dynamic-exponent level sets (App. A), written out: sign bit, one fraction cell per
+# exponent step 10^-i represented by the mean of its boundaries on [0.1, 1], plus 0 and 1.
+DE_LEVELS = {2: [-0.55, 0.0, 0.55, 1.0],
+             3: [-0.775, -0.325, -0.055, 0.0, 0.055, 0.325, 0.775, 1.0],
+             4: [-0.8875, -0.6625, -0.4375, -0.2125, -0.0775, -0.0325, -0.0055, 0.0,
+                 0.0055, 0.0325, 0.0775, 0.2125, 0.4375, 0.6625, 0.8875, 1.0]}
+
 
 def fresh_unpacked(so, n, cfg):
     nblk = -(-n // cfg.block_size)
@@ -33,7 +40,7 @@ def brute_step(so, p, g, mc, ms, vc, vs, va, step, cfg):
     n = p.size
     b1, b2 = float(np.float32(cfg.beta1)), float(np.float32(cfg.beta2))
     lr, wd, eps = (float(np.float32(x)) for x in (cfg.lr, cfg.weight_decay, cfg.eps))
-    mlevels = np.array([k / L for k in range(-L, L + 1)])
+    mlevels = np.array(DE_LEVELS[bm]) if cfg.m_codebook else np.array([k / L for k in range(-L, L + 1)])
     out_p = np.empty(n)
     out_mc, out_vc = np.empty(n, int), np.empty(n, int)
     clear = np.ones(n, bool)
@@ -57,7 +64,7 @@ def brute_step(so, p, g, mc, ms, vc, vs, va, step, cfg):
             dist = np.abs((mh / dm)[:, None] - mlevels[None, :])
             out_mc[sl] = np.argmin(dist, axis=1)
             srt = np.sort(dist, axis=1)
-            clear[sl] &= (srt[:, 1] - srt[:, 0]) > 2e-5
+            clear[sl] &= (srt[:, 1] - srt[:, 0]) > 2e-5 * np.maximum(srt[:, 0] + srt[:, 1], 1e-3)
         if dv < 2.0 ** -100:
             out_vs[blk], out_va[blk] = 0, 1
             out_vc[sl] = 0
@@ -83,11 +90,12 @@ def brute_step(so, p, g, mc, ms, vc, vs, va, step, cfg):
 
 @pytest.mark.parametrize("bm,bv,B", [(2, 2, 64), (2, 3, 128), (3, 3, 128), (4, 4, 128),
                                      (4, 2, 64), (3, 4, 64), (2, 4, 128), (4, 3, 128), (3, 2, 64)])
-def test_step_against_brute_force_on_tiny_tensors(so, bm, bv, B):
+@pytest.mark.parametrize("codebook", (0, 1))
+def test_step_against_brute_force_on_tiny_tensors(so, bm, bv, B, codebook):
     rng = np.random.default_rng(1000 + 16 * bm + bv)
     for n in (B, 2 * B + 17, 256, 5):
         cfg = so.make_config(bits_m=bm, bits_v=bv, block_size=B, beta1=0.5 if bm == 2 else 0.8,
-                             seed=9, index_offset=8 * 123456789)
+                             seed=9, index_offset=8 * 123456789, m_codebook=codebook)
         p = (rng.standard_normal(n) * 0.02).astype(np.float32)
         mc, ms, vc, vs, va = fresh_unpacked(so, n, cfg)
         unclear = 0
