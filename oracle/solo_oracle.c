@@ -128,7 +128,8 @@ int so_de_levels(uint32_t bits, int is_signed, double *out)
     int n = 0;
     for (int i = 0; i < nsb; ++i) {
         const int cells = is_signed ? (1 << i) : (1 << (i + 1));
-        const double scale = pow(10.0, (double)(-(nsb - 1) + i));
+        static const double tenth[8] = {1.0, 0.1, 0.01, 0.001, 1e-4, 1e-5, 1e-6, 1e-7};
+        const double scale = tenth[(nsb - 1) - i];
         for (int c = 0; c < cells; ++c) {
             const double lo = 0.1 + 0.9 * (double)c / (double)cells;
             const double hi = 0.1 + 0.9 * (double)(c + 1) / (double)cells;
