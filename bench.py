@@ -86,7 +86,8 @@ def cpu_baseline(w, sample, steps=3):
     threads = min(so.max_threads(), int(os.environ.get("OMP_NUM_THREADS", "1000")))
     cfg = so.make_config(bits_m=w.bits_m, bits_v=w.bits_v, block_size=w.block_size, beta1=w.beta1,
                          beta2=w.beta2, lr=w.lr, eps=w.eps, weight_decay=w.weight_decay,
-                         quantile_p=w.quantile_p, seed=synth.SEED_XI)
+                         quantile_p=w.quantile_p, seed=synth.SEED_XI,
+                         m_codebook=1 if w.m_codebook == "de" else 0)
     p = synth.make_params(sample)
     st = so.State(sample, cfg)
     times = []
@@ -157,7 +158,8 @@ def main():
     cfg = solo.make_config(w.bits_m, w.bits_v, w.block_size,
                            solo.SOLO_GRAD_BF16 if w.grad_dtype == "bf16" else solo.SOLO_GRAD_FP32,
                            lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
-                           weight_decay=w.weight_decay, quantile_p=w.quantile_p, seed=synth.SEED_XI)
+                           weight_decay=w.weight_decay, quantile_p=w.quantile_p, seed=synth.SEED_XI,
+                           flags=solo.SOLO_FLAG_STOCHASTIC | (solo.SOLO_FLAG_M_DYNAMIC_EXPONENT if w.m_codebook == "de" else 0))
     gdtype = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
     p = device_params(torch, w, synth.SEED_PARAM)
     grads = [device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(w.config_id, k), gdtype)
@@ -199,6 +201,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "params": n, "bits_m": w.bits_m, "bits_v": w.bits_v,
                    "block_size": w.block_size, "grad_dtype": w.grad_dtype, "beta1": w.beta1,
+                   "m_codebook": w.m_codebook,
                    "bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),

@@ -32,7 +32,9 @@
  *   v_scale  float[nb]   Delta_v = max v of the block
  *   v_base   float[nb]   alpha of the block, in (0, 1]
  *   A 1st-moment code c in [0, 2L], L = 2^(bits_m-1)-1, stands for the level
- *   (c - L) / L; a 2nd-moment code q in [0, 2^bits_v - 1] for alpha^q.
+ *   (c - L) / L; with SOLO_FLAG_M_DYNAMIC_EXPONENT a code in [0, 2L+1] indexes the
+ *   increasing signed dynamic-exponent levels (code L is 0, code 2L+1 is +1, there
+ *   is no level -1).  A 2nd-moment code q in [0, 2^bits_v - 1] stands for alpha^q.
  *   param, grad and the code buffers must be 16-byte aligned, the scale
  *   buffers 4-byte aligned.
  */
@@ -57,6 +59,9 @@ enum { SOLO_GRAD_FP32 = 0, SOLO_GRAD_BF16 = 1 };
 
 /* flags */
 #define SOLO_FLAG_STOCHASTIC 1u   /* xi ~ U(-0.5, 0.5); clear = xi = 0 */
+#define SOLO_FLAG_M_DYNAMIC_EXPONENT 2u /* 1st moment uses the signed dynamic-exponent levels of
+                                          App. A (the paper's own 4/2-bit and 2-bit AdamW, Sec. 3.4)
+                                          instead of the signed linear ones */
 
 typedef struct solo_config {
     uint32_t bits_m;       /* 2, 3 or 4: signed linear codes (App. A)                  */

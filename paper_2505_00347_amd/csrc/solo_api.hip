@@ -9,12 +9,15 @@
 
 namespace solo {
 
-template <int BM>
+template <int BM, bool MDE>
 hipError_t launch_step(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
                        bool has_tail, hipStream_t stream);
-template <> hipError_t launch_step<2>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<3>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<4>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<2, false>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<3, false>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<4, false>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<2, true>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<3, true>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+template <> hipError_t launch_step<4, true>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
 
 static bool bits_ok(uint32_t b) { return b >= 2 && b <= 4; }
 
@@ -28,7 +31,7 @@ static bool config_ok(const solo_config *c)
     if (!(c->quantile_p >= 0.0f && c->quantile_p < 1.0f)) return false;
     if (!(c->eps >= 0.0f) || !isfinite(c->eps)) return false;
     if (!isfinite(c->lr) || !isfinite(c->weight_decay)) return false;
-    if ((c->flags & ~SOLO_FLAG_STOCHASTIC) != 0 || c->reserved != 0) return false;
+    if ((c->flags & ~(SOLO_FLAG_STOCHASTIC | SOLO_FLAG_M_DYNAMIC_EXPONENT)) != 0 || c->reserved != 0) return false;
     if (c->index_offset % 8 != 0) return false;
     return true;
 }
@@ -188,11 +191,16 @@ int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_
 
     const bool has_tail = (n % solo::kTile) != 0;
     const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;
+    const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
+    hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (cfg->bits_m) {
-    case 2: e = solo::launch_step<2>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, (hipStream_t)stream); break;
-    case 3: e = solo::launch_step<3>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, (hipStream_t)stream); break;
-    case 4: e = solo::launch_step<4>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, (hipStream_t)stream); break;
+    case 2: e = mde ? solo::launch_step<2, true>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s)
+                    : solo::launch_step<2, false>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s); break;
+    case 3: e = mde ? solo::launch_step<3, true>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s)
+                    : solo::launch_step<3, false>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s); break;
+    case 4: e = mde ? solo::launch_step<4, true>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s)
+                    : solo::launch_step<4, false>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s); break;
     default: return SOLO_E_UNSUPPORTED;
     }
     return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;

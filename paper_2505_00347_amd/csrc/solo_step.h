@@ -202,6 +202,43 @@ __device__ __forceinline__ uint32_t extract8(uint32_t w0, uint32_t w1, uint32_t 
     return w0 >> (BITS * slot);   // 2-bit: slot 0 or 8; 4-bit: slot 0
 }
 
+// Signed dynamic-exponent (DE) levels of the 1st moment (App. A of the paper): the first bit
+// is the sign, the other b-1 bits spend E leading zeros on the exponent 10^-E, one indicator
+// bit, and the rest on a linear fraction over [0.1, 1].  Exponent step i (scale 10^(-(b-2)+i))
+// owns 2^i fraction cells, each represented by the mean of its boundaries, and the two codes
+// left over are the levels 0 and 1.  Non-negative levels in increasing order:
+// pos(0) = 0, pos(1..L) the cell means, pos(L+1) = 1, L = 2^(b-1) - 1; the negative side
+// mirrors pos(1..L) (there is no level -1).
+template <int BM>
+struct DeLevels {
+    static constexpr int L = (1 << (BM - 1)) - 1;
+    static constexpr double pos(int j)
+    {
+        if (j <= 0) return 0.0;
+        if (j > L) return 1.0;
+        constexpr double tenth[8] = {1.0, 0.1, 0.01, 0.001, 1e-4, 1e-5, 1e-6, 1e-7};
+        int i = 0, first = 1;                       // exponent step i holds cells [first, first + 2^i)
+        while (j >= first + (1 << i)) { first += (1 << i); ++i; }
+        const int cells = 1 << i, c = j - first;
+        const double lo = 0.1 + 0.9 * (double)c / (double)cells;
+        const double hi = 0.1 + 0.9 * (double)(c + 1) / (double)cells;
+        return tenth[(BM - 2) - i] * (lo + hi) / 2.0;
+    }
+    // midpoint between pos(k) and pos(k+1), the rounding boundary of the magnitude
+    static constexpr float mid(int k) { return (float)((pos(k) + pos(k + 1)) / 2.0); }
+    // level of a code in [0, 2L+1] for a run-time code (used once per wavefront)
+    __device__ static float level(uint32_t code)
+    {
+        float r = 0.0f;
+#pragma unroll
+        for (int j = 1; j <= L + 1; ++j) {
+            r = (code == (uint32_t)(L + j)) ? (float)pos(j) : r;
+            if (j <= L) r = (code == (uint32_t)(L - j)) ? -(float)pos(j) : r;
+        }
+        return r;
+    }
+};
+
 // ------------------------------------------------------------------- kernel
 
 // LDS accessed through 32-bit byte addresses, so that a table index can be
@@ -281,7 +318,7 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int BM, int BV, int B, bool BF16, bool TAIL>
+template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL>
 __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const StepArgs a)
 {
     constexpr int G = B / 8;                       // lanes per block
@@ -292,7 +329,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     constexpr int CM = 32 / BM, CV = 32 / BV;      // codes per word
     constexpr int MW = kTile / CM, VW = kTile / CV; // words per super-tile
     constexpr int VT = K + 1;                      // entries of a block's v level table (4, 8, 16)
-    constexpr int MT = 2 * L + 1;                  // entries of a block's m level table (3, 7, 15)
+    constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1; // entries of a block's m level table (3, 7, 15; DE: 4, 8, 16)
     constexpr int MTS = 16;                        // stride of the m tables
     constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
     constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;   // byte-index masks
@@ -381,6 +418,13 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     uint32_t wm = (lane * 8u) / CM, sm = (lane * 8u) % CM;
     uint32_t wv = (lane * 8u) / CV, sv = (lane * 8u) % CV;
 
+    // DE codebook: the levels of the table entries this lane fills (entries lig, lig + G)
+    float de_level[(16 + G - 1) / G];
+    if (MDE) {
+#pragma unroll
+        for (int r = 0; r < (MT + G - 1) / G; ++r) de_level[r] = DeLevels<BM>::level(lig + r * G);
+    }
+
 #pragma unroll 1
     for (int it = 0; it < kIters; ++it) {
         const uint32_t e_loc = (uint32_t)it * kIter + lane * 8u;   // element inside the tile
@@ -418,7 +462,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 #pragma unroll
             for (int r = 0; r < (MT + G - 1) / G; ++r) {
                 const uint32_t c = lig + r * G;
-                if (c < MT) my_tm[c] = (float)((int)c - L) * s_m;
+                if (c < MT) my_tm[c] = MDE ? de_level[r] * dm_old : (float)((int)c - L) * s_m;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -530,7 +574,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
         for (uint32_t k = 0; k < a.rank_full; ++k) extract_round(k);
 
         // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
-        const float num = (lane & 1u) ? (float)L : u2f(xp_bits);
+        const float num = (lane & 1u) ? (MDE ? 1.0f : (float)L) : u2f(xp_bits);
         const float den = (lane & 1u) ? dm : dv;
         const float quo = num / den;
         float rho = u2f(dpp<0xA0>(f2u(quo)));        // quad_perm [0,0,2,2]
@@ -573,9 +617,23 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
         // ---- encode: codes rounded in the float domain, four to an accumulator
         // m: code - L = rint(m^ * L/Delta_m) in [-L, L];  v: code + 1 = floor(log_alpha(v^/Delta_v) + 1.5 + xi)
         float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
+        uint32_t m8_de = 0;
 #pragma unroll
         for (int j = 7; j >= 0; --j) {
-            float tm = __builtin_rintf(mh[j] * inv_s);
+            float tm = 0.0f;
+            if (!MDE) {
+                tm = __builtin_rintf(mh[j] * inv_s);
+            } else {
+                // DE: nearest level on the magnitude; inv_s = 1/Delta_m.  j = #midpoints below |z|
+                const float z = mh[j] * inv_s;
+                const float az = __builtin_fabsf(z);
+                uint32_t cnt = 0;
+#pragma unroll
+                for (int k = 0; k <= L; ++k) cnt += (az > DeLevels<BM>::mid(k)) ? 1u : 0u;
+                uint32_t code = (z < 0.0f) ? (uint32_t)L - umin(cnt, (uint32_t)L) : (uint32_t)L + cnt;
+                if (TAIL && !ok[j]) code = 0;
+                m8_de |= code << (BM * j);
+            }
             const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, X + (uint32_t)j * Y, 9u));
             const float ratio = __builtin_fmaf(vh[j], rdv, bias);
             float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, f));
@@ -586,7 +644,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
         }
         constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));   // L * sum 2^(BM j), j < 4
         constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
-        const uint32_t m8 = (uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM));
+        const uint32_t m8 = MDE ? m8_de : ((uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM)));
         const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
 
         // ---- update the state image in place: XOR turns this lane's old fields into the new
@@ -634,37 +692,37 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     }
 }
 
-// Host-side launcher of one instantiation family (fixed bits_m); defined in
-// solo_step_m{2,3,4}.hip so that the families compile in parallel.
-template <int BM>
+// Host-side launcher of one instantiation family (fixed bits_m and 1st-moment codebook);
+// defined in solo_step_m{2,3,4}{,_de}.hip so that the families compile in parallel.
+template <int BM, bool MDE>
 hipError_t launch_step(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
                        bool has_tail, hipStream_t stream);
 
-template <int BM, int BV, int B, bool BF16>
+template <int BM, int BV, int B, bool BF16, bool MDE>
 hipError_t launch_one(const StepArgs &args, bool has_tail, hipStream_t stream)
 {
     if (args.n_tiles_full) {
         const uint64_t grid = args.wg_per_xcd * kXcds;
-        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, false>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
+        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, false>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (has_tail) {
-        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, true>), dim3(1), dim3(64), 0, stream, args);
+        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true>), dim3(1), dim3(64), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-template <int BM>
+template <int BM, bool MDE>
 hipError_t launch_step_impl(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
                             bool has_tail, hipStream_t stream)
 {
 #define SOLO_CASE(BV_, B_)                                                             \
     if (bits_v == BV_ && block_size == B_)                                             \
-        return bf16 ? launch_one<BM, BV_, B_, true>(args, has_tail, stream)            \
-                    : launch_one<BM, BV_, B_, false>(args, has_tail, stream);
+        return bf16 ? launch_one<BM, BV_, B_, true, MDE>(args, has_tail, stream)       \
+                    : launch_one<BM, BV_, B_, false, MDE>(args, has_tail, stream);
     SOLO_CASE(2, 64) SOLO_CASE(2, 128) SOLO_CASE(3, 64) SOLO_CASE(3, 128) SOLO_CASE(4, 64) SOLO_CASE(4, 128)
 #undef SOLO_CASE
     return hipErrorInvalidValue;

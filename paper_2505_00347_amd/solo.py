@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsolo.so")
 SOLO_OK, SOLO_E_INVALID, SOLO_E_UNSUPPORTED, SOLO_E_HIP = 0, -1, -2, -3
 SOLO_GRAD_FP32, SOLO_GRAD_BF16 = 0, 1
 SOLO_FLAG_STOCHASTIC = 1
+SOLO_FLAG_M_DYNAMIC_EXPONENT = 2
 
 
 class solo_config(C.Structure):

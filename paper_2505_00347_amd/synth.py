@@ -81,6 +81,7 @@ class Workload:
     weight_decay: float = 0.01
     quantile_p: float = 0.1
     steps: int = 10
+    m_codebook: str = "linear"   # "linear" | "de" (signed dynamic exponent, the paper's own variants)
     extra: dict = field(default_factory=dict)
 
     @property
@@ -103,6 +104,13 @@ def workload(name):
     if name == "c5_llama7b_2bit_3bit":
         return Workload(name, 5, llama_7b_shapes(), 2, 3, 128, 0.5, "bf16",
                         "normal_outliers", 1e-4)
+    # the paper's own two variants (Sec. 3.4) on the LLaMA-7B shapes
+    if name == "paper_4_2bit_llama7b":
+        return Workload(name, 6, llama_7b_shapes(), 4, 2, 128, 0.8, "bf16", "normal_outliers", 1e-4,
+                        m_codebook="de")
+    if name == "paper_2bit_llama7b":
+        return Workload(name, 7, llama_7b_shapes(), 2, 2, 128, 0.5, "bf16", "normal_outliers", 1e-4,
+                        m_codebook="de")
     raise KeyError(name)
 
 

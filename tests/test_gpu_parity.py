@@ -70,13 +70,14 @@ class GpuSide:
 
 
 def make_cfgs(so, solo, bm, bv, B, bf16=False, stochastic=1, beta1=None, p=0.1, seed=42, off=0,
-              lr=1e-3, wd=0.01, eps=1e-8, beta2=0.999):
+              lr=1e-3, wd=0.01, eps=1e-8, beta2=0.999, de=False):
     beta1 = {2: 0.5, 3: 0.6, 4: 0.8}[bm] if beta1 is None else beta1
     oc = so.make_config(bits_m=bm, bits_v=bv, block_size=B, stochastic=stochastic, lr=lr, beta1=beta1,
-                        beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p, seed=seed, index_offset=off)
+                        beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p, seed=seed, index_offset=off,
+                        m_codebook=1 if de else 0)
     gc = solo.make_config(bits_m=bm, bits_v=bv, block_size=B, grad_dtype=1 if bf16 else 0, lr=lr,
                           beta1=beta1, beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p,
-                          flags=1 if stochastic else 0, seed=seed, index_offset=off)
+                          flags=(1 if stochastic else 0) | (2 if de else 0), seed=seed, index_offset=off)
     return oc, gc
 
 
@@ -205,6 +206,30 @@ def test_config5_shape_2bit_m_3bit_v_bf16(so, gpu):
              std=1e-4, seed0=5100)
 
 
+# ------------------------------------- the paper's own variants: dynamic-exponent 1st moment
+
+def test_paper_4_2bit_adamw_de_first_moment(so, gpu):
+    """SOLO 4/2-bit AdamW (Sec. 3.4): 4-bit signed dynamic-exponent m with beta1 = 0.8,
+    2-bit logarithmic v, block 128."""
+    run_teacher_forced(so, gpu, 1 << 20, 4, 2, 128, steps=6, seed0=6000, de=True, beta1=0.8)
+    flips, tainted = run_free(so, gpu, 1 << 19, 4, 2, 128, steps=10, seed0=6100, de=True, beta1=0.8)
+    print(f"4/2-bit free-running: {flips} flips, {tainted} blocks diverged")
+
+
+def test_paper_2bit_adamw_de_first_moment(so, gpu):
+    """SOLO 2-bit AdamW (Sec. 3.4): 2-bit signed dynamic-exponent m with beta1 = 0.5 (0.1 from
+    scratch), 2-bit logarithmic v."""
+    run_teacher_forced(so, gpu, 1 << 20, 2, 2, 128, steps=6, seed0=6200, de=True, beta1=0.5, bf16=True, std=1e-4,
+                       kind="normal_outliers")
+    run_free(so, gpu, 1 << 19, 2, 2, 128, steps=10, seed0=6300, de=True, beta1=0.1)
+
+
+@pytest.mark.parametrize("bm", (2, 3, 4))
+def test_dynamic_exponent_all_formats(so, gpu, bm):
+    for bv, B, bf16, n in ((3, 128, False, 3 * 2560 + 777), (4, 64, True, 2 * 2560 + 1283), (2, 64, False, 641)):
+        run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=4, seed0=50 + bm, de=True)
+
+
 # ------------------------------------------------------ every format, ragged sizes
 
 @pytest.mark.parametrize("bm", (2, 3, 4))
@@ -256,11 +281,13 @@ def special_grads(n, B, seed):
     return g
 
 
-@pytest.mark.parametrize("bm,bv,B,bf16", [(2, 3, 128, False), (4, 4, 64, False), (3, 2, 128, True)])
-def test_degenerate_blocks(so, gpu, bm, bv, B, bf16):
+@pytest.mark.parametrize("bm,bv,B,bf16,de", [(2, 3, 128, False, False), (4, 4, 64, False, False),
+                                              (3, 2, 128, True, False), (4, 2, 128, False, True),
+                                              (2, 2, 64, True, True)])
+def test_degenerate_blocks(so, gpu, bm, bv, B, bf16, de):
     from paper_2505_00347_amd import synth
     n = 24 * B + 11
-    oc, gc = make_cfgs(so, gpu, bm, bv, B, bf16)
+    oc, gc = make_cfgs(so, gpu, bm, bv, B, bf16, de=de)
     p = synth.make_params(n)
     st = so.State(n, oc)
     side = GpuSide(gpu, n, gc)
@@ -294,7 +321,7 @@ def test_empty_and_invalid_arguments(gpu):
     assert solo.solo_adamw_step(0, g, *st.buffers(), 2560, 1, cfg, check=False) == solo.SOLO_E_INVALID
     for field, value in (("bits_m", 5), ("bits_v", 1), ("block_size", 96), ("grad_dtype", 2),
                          ("beta1", 1.0), ("beta2", -0.1), ("quantile_p", 1.0), ("eps", -1.0),
-                         ("flags", 2), ("reserved", 1), ("index_offset", 4), ("lr", float("nan"))):
+                         ("flags", 4), ("reserved", 1), ("index_offset", 4), ("lr", float("nan"))):
         bad = solo.make_config(2, 3, 128, 1)
         setattr(bad, field, value)
         assert solo.solo_adamw_step(*args, 2560, 1, bad, check=False) == solo.SOLO_E_INVALID, field
