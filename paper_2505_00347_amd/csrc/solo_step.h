@@ -224,17 +224,24 @@ struct DeLevels {
         const double hi = 0.1 + 0.9 * (double)(c + 1) / (double)cells;
         return tenth[(BM - 2) - i] * (lo + hi) / 2.0;
     }
-    // midpoint between pos(k) and pos(k+1), the rounding boundary of the magnitude
-    static constexpr float mid(int k) { return (float)((pos(k) + pos(k + 1)) / 2.0); }
-    // level of a code in [0, 2L+1] for a run-time code (used once per wavefront)
+    // Tables evaluated at compile time: the signed levels by code (2L + 2 of them) and the
+    // midpoints between neighbouring non-negative levels (the rounding boundaries of |z|).
+    struct Tables {
+        float level[2 * L + 2];
+        float mid[L + 1];
+        constexpr Tables() : level(), mid()
+        {
+            for (int c = 0; c < 2 * L + 2; ++c) level[c] = c >= L ? (float)pos(c - L) : -(float)pos(L - c);
+            for (int k = 0; k <= L; ++k) mid[k] = (float)((pos(k) + pos(k + 1)) / 2.0);
+        }
+    };
+    static constexpr Tables tab = Tables();
+    // level of a run-time code (used once per wavefront): a select chain over literals
     __device__ static float level(uint32_t code)
     {
         float r = 0.0f;
 #pragma unroll
-        for (int j = 1; j <= L + 1; ++j) {
-            r = (code == (uint32_t)(L + j)) ? (float)pos(j) : r;
-            if (j <= L) r = (code == (uint32_t)(L - j)) ? -(float)pos(j) : r;
-        }
+        for (int c = 0; c < 2 * L + 2; ++c) r = (code == (uint32_t)c) ? tab.level[c] : r;
         return r;
     }
 };
@@ -629,7 +636,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
                 const float az = __builtin_fabsf(z);
                 uint32_t cnt = 0;
 #pragma unroll
-                for (int k = 0; k <= L; ++k) cnt += (az > DeLevels<BM>::mid(k)) ? 1u : 0u;
+                for (int k = 0; k <= L; ++k) cnt += (az > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
                 uint32_t code = (z < 0.0f) ? (uint32_t)L - umin(cnt, (uint32_t)L) : (uint32_t)L + cnt;
                 if (TAIL && !ok[j]) code = 0;
                 m8_de |= code << (BM * j);
