@@ -16,6 +16,8 @@
  *   2. EMA update   m^ = beta1 m~ + (1-beta1) g         (Sec. 3.1, Eqs. 2-4)
  *                   v^ = beta2 v~ + (1-beta2) g^2
  *   3. parameter    decoupled-decay Adam step driven by m^ and v^
+ *                   (so_config.optimizer also offers Adam with the decay inside the
+ *                   gradient, and AdaBelief, whose 2nd EMA follows (g - m^)^2 + eps)
  *   4. block stats  Delta_m' = max|m^|, Delta_v' = max v^,
  *                   x_p = p-quantile of v^, alpha' = (x_p/Delta_v')^(1/(2^b-1))
  *                                               (Sec. 3.2.2, adaptive base)
@@ -55,8 +57,16 @@ typedef struct so_config {
     uint64_t seed;        /* key of the xi stream                              */
     uint64_t index_offset;/* global index of element 0 (multiple of 8)         */
     uint32_t m_codebook;  /* 1st-moment levels: 0 signed linear, 1 signed dynamic exponent */
+    uint32_t optimizer;   /* SO_ADAMW, SO_ADAM_L2 or SO_ADABELIEF                         */
+    float grad_scale;     /* every gradient is multiplied by it first (loss-scale         */
+                          /* reciprocal, clipping factor); 1 leaves it unchanged          */
     uint32_t pad_;
 } so_config;
+
+/* The EMA optimizers the quantizers are applied to (Sec. 4.2, "Generalizability"):
+ * AdamW (decoupled decay), Adam (the decay enters the gradient as lambda * p) and
+ * AdaBelief (the unsigned EMA tracks (g - m^)^2 and gains eps at every step). */
+enum { SO_ADAMW = 0, SO_ADAM_L2 = 1, SO_ADABELIEF = 2 };
 
 #define SO_MAX_BLOCK 4096
 /* A block whose maximum is below this is stored as an all-zero block, so that
@@ -390,6 +400,7 @@ int so_step_unpacked(float *param, const float *grad,
     if (B == 0 || B > SO_MAX_BLOCK || step == 0) return -1;
     if (cfg->bits_m < 2 || cfg->bits_m > 16 || cfg->bits_v < 2 || cfg->bits_v > 16) return -1;
     if (cfg->m_codebook > 1 || (cfg->m_codebook == 1 && cfg->bits_m > 8)) return -1;
+    if (cfg->optimizer > SO_ADABELIEF) return -1;
     const uint64_t nblk = (n + B - 1) / B;
     const float beta1 = cfg->beta1, beta2 = cfg->beta2;
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
@@ -397,7 +408,8 @@ int so_step_unpacked(float *param, const float *grad,
      * the bias-corrected root. */
     const double bc1 = 1.0 - pow((double)beta1, (double)step);
     const double bc2 = 1.0 - pow((double)beta2, (double)step);
-    const double decay = 1.0 - (double)cfg->lr * (double)cfg->weight_decay;
+    const double decay = cfg->optimizer == SO_ADAM_L2
+                             ? 1.0 : 1.0 - (double)cfg->lr * (double)cfg->weight_decay;
     const double step_size = (double)cfg->lr / bc1;
     uint32_t keys[4];
     so_xi_keys(cfg->seed, step, keys);
@@ -411,14 +423,22 @@ int so_step_unpacked(float *param, const float *grad,
         const uint32_t nb = (uint32_t)((n - i0) < B ? (n - i0) : B);
         for (uint32_t k = 0; k < nb; ++k) {
             const uint64_t i = i0 + k;
-            const float g = grad[i];
+            float g = grad[i] * cfg->grad_scale;
+            if (cfg->optimizer == SO_ADAM_L2) g = fmaf(cfg->weight_decay, param[i], g);
             const float mt = cfg->m_codebook ? so_dequant_m_de(m_codes[i], m_scale[blk], cfg->bits_m)
                                              : so_dequant_m(m_codes[i], m_scale[blk], cfg->bits_m);
             const float vt = so_dequant_v(v_codes[i], v_scale[blk], v_base[blk], cfg->bits_v);
             /* EMA (Sec. 3.1): the signal term is rounded, then one fused
              * multiply-add joins it to beta * state. */
             mh[k] = fmaf(beta1, mt, omb1 * g);
-            vh[k] = fmaf(beta2, vt, omb2 * (g * g));
+            if (cfg->optimizer == SO_ADABELIEF) {
+                /* the signal of the unsigned EMA is the squared distance of the gradient
+                 * from the fresh 1st moment, and eps is added to the state itself */
+                const float d = g - mh[k];
+                vh[k] = fmaf(beta2, vt, omb2 * (d * d)) + cfg->eps;
+            } else {
+                vh[k] = fmaf(beta2, vt, omb2 * (g * g));
+            }
             const double denom = sqrt((double)vh[k]) / sqrt(bc2) + (double)cfg->eps;
             const double pd = (double)param[i] * decay - step_size * (double)mh[k] / denom;
             param[i] = (float)pd;
@@ -433,6 +453,31 @@ int so_step_unpacked(float *param, const float *grad,
     }
     (void)threads;
     return 0;
+}
+
+/* ------------------------------------------------------ 16-bit weight copy */
+
+/* The bfloat16 nearest to each binary32 value, ties to the even mantissa (the
+ * 16-bit weights that mixed-precision training keeps next to the 32-bit ones,
+ * Sec. 1).  The two candidates are x with its low 16 bits cleared and the next
+ * larger magnitude; infinities and NaNs keep their upper half. */
+void so_round_bf16(const float *x, uint16_t *out, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &x[i], 4);
+        uint32_t lo = u & 0xFFFF0000u, hi = lo + 0x10000u;
+        if ((u & 0x7F800000u) == 0x7F800000u) { out[i] = (uint16_t)(u >> 16) | ((u & 0xFFFFu) ? 0x40u : 0u); continue; }
+        float flo, fhi;
+        memcpy(&flo, &lo, 4);
+        memcpy(&fhi, &hi, 4);                    /* may be +-inf: overflow rounds there */
+        double dlo = fabs((double)x[i] - (double)flo);
+        double dhi = (hi & 0x7F800000u) == 0x7F800000u
+                         ? fabs(ldexp(1.0, 128) - fabs((double)x[i]))   /* distance to the value inf stands for */
+                         : fabs((double)fhi - (double)x[i]);
+        uint32_t pick = dlo < dhi ? lo : dhi < dlo ? hi : ((lo >> 16) & 1u) ? hi : lo;
+        out[i] = (uint16_t)(pick >> 16);
+    }
 }
 
 /* --------------------------------------------------------------- packing */

@@ -36,14 +36,19 @@ class Config(C.Structure):
                 ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float), ("weight_decay", C.c_float), ("quantile_p", C.c_float),
                 ("seed", C.c_uint64), ("index_offset", C.c_uint64),
-                ("m_codebook", C.c_uint32), ("pad_", C.c_uint32)]
+                ("m_codebook", C.c_uint32), ("optimizer", C.c_uint32),
+                ("grad_scale", C.c_float), ("pad_", C.c_uint32)]
+
+
+ADAMW, ADAM_L2, ADABELIEF = 0, 1, 2
 
 
 def make_config(bits_m=4, bits_v=4, block_size=128, stochastic=1, lr=1e-3, beta1=0.8,
                 beta2=0.999, eps=1e-8, weight_decay=0.01, quantile_p=0.1, seed=42,
-                index_offset=0, m_codebook=0):
+                index_offset=0, m_codebook=0, optimizer=ADAMW, grad_scale=1.0):
     return Config(bits_m, bits_v, block_size, stochastic, lr, beta1, beta2, eps,
-                  weight_decay, quantile_p, seed, index_offset, m_codebook, 0)
+                  weight_decay, quantile_p, seed, index_offset, m_codebook, optimizer,
+                  grad_scale, 0)
 
 
 _lib = None
@@ -107,6 +112,7 @@ def _declare(L):
     L.so_step_packed.argtypes = [_f32p, _f32p, _u32p, _f32p, _u32p, _f32p, _f32p, C.c_uint64,
                                  C.c_uint64, C.POINTER(Config), C.c_void_p, C.c_int]
     L.so_max_threads.restype = C.c_int; L.so_max_threads.argtypes = []
+    L.so_round_bf16.restype = None; L.so_round_bf16.argtypes = [_f32p, _u16p, C.c_uint64]
 
 
 # ------------------------------------------------------------ scalar helpers
@@ -187,6 +193,14 @@ def quant_v_block(x, bits, p=0.1, stochastic=1, seed=42, step=1, i0=0, want_marg
                            margin.ctypes.data if want_margin else None)
     out = (codes, np.float32(scale.value), np.float32(base.value))
     return out + (margin,) if want_margin else out
+
+
+def round_bf16(x):
+    """bfloat16 bit patterns nearest to the float32 values (ties to even)."""
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.zeros(x.size, np.uint16)
+    lib().so_round_bf16(x.reshape(-1), out, x.size)
+    return out
 
 
 # ------------------------------------------------------------------ packing

@@ -48,13 +48,19 @@ def brute_step(so, p, g, mc, ms, vc, vs, va, step, cfg):
     for blk in range(ms.size):
         sl = slice(blk * B, min(n, (blk + 1) * B))
         nb = sl.stop - sl.start
-        gg = g[sl].astype(np.float64)
+        gg = g[sl].astype(np.float64) * float(np.float32(cfg.grad_scale))
+        if cfg.optimizer == so.ADAM_L2:
+            gg = gg + wd * p[sl]
         mt = mlevels[mc[sl]] * float(ms[blk])
         vt = np.power(float(va[blk]), vc[sl].astype(np.float64)) * float(vs[blk])
         mh = b1 * mt + (1 - b1) * gg
-        vh = b2 * vt + (1 - b2) * gg * gg
+        if cfg.optimizer == so.ADABELIEF:
+            vh = b2 * vt + (1 - b2) * (gg - mh) ** 2 + eps
+        else:
+            vh = b2 * vt + (1 - b2) * gg * gg
         bc1, bc2 = 1 - b1 ** step, 1 - b2 ** step
-        out_p[sl] = p[sl] * (1 - lr * wd) - lr * (mh / bc1) / (np.sqrt(vh / bc2) + eps)
+        keep = 1.0 if cfg.optimizer == so.ADAM_L2 else 1 - lr * wd
+        out_p[sl] = p[sl] * keep - lr * (mh / bc1) / (np.sqrt(vh / bc2) + eps)
         dm, dv = np.max(np.abs(mh)), np.max(vh)
         out_ms[blk], out_vs[blk] = dm, dv
         if dm < 2.0 ** -100:
@@ -113,6 +119,32 @@ def test_step_against_brute_force_on_tiny_tensors(so, bm, bv, B, codebook):
             assert np.all(np.abs(mc.astype(int) - wmc) <= 1) and np.all(np.abs(vc.astype(int) - wvc) <= 1)
             unclear += int(np.sum(~clear))
         assert unclear <= max(2, n // 50)
+
+
+@pytest.mark.parametrize("optimizer", ("ADAM_L2", "ADABELIEF"))
+@pytest.mark.parametrize("bm,bv,B,codebook", [(2, 3, 128, 0), (4, 2, 128, 1), (3, 3, 64, 0)])
+def test_other_optimizers_against_brute_force(so, optimizer, bm, bv, B, codebook):
+    """Adam with the decay inside the gradient and AdaBelief, with a gradient scale, against
+    the same brute-force step (Sec. 4.2 applies the quantizers to AdaBelief unchanged)."""
+    rng = np.random.default_rng(77 + bm + 8 * bv)
+    n = 2 * B + 17
+    cfg = so.make_config(bits_m=bm, bits_v=bv, block_size=B, beta1=0.5 if bm == 2 else 0.8, seed=5,
+                         m_codebook=codebook, optimizer=getattr(so, optimizer), grad_scale=1 / 1024,
+                         weight_decay=0.1, eps=1e-8 if optimizer == "ADAM_L2" else 1e-12)
+    p = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    mc, ms, vc, vs, va = fresh_unpacked(so, n, cfg)
+    unclear = 0
+    for step in range(1, 7):
+        g = (rng.standard_normal(n) * 1.024).astype(np.float32)
+        want = brute_step(so, p, g, mc.astype(int), ms, vc.astype(int), vs, va, step, cfg)
+        so.step_unpacked(p, g, mc, ms, vc, vs, va, step, cfg)
+        wp, wmc, wms, wvc, wvs, wva, clear = want
+        assert np.allclose(p, wp, rtol=2e-6, atol=1e-9)
+        assert np.allclose(ms, wms, rtol=1e-6) and np.allclose(vs, wvs, rtol=1e-6)
+        assert np.allclose(va, wva, rtol=1e-6)
+        assert np.array_equal(mc[clear], wmc[clear]) and np.array_equal(vc[clear], wvc[clear])
+        unclear += int(np.sum(~clear))
+    assert unclear <= max(2, n // 50)
 
 
 # --------------------------------------------------------------- closed forms
@@ -201,6 +233,132 @@ def test_reduces_to_adamw_as_codes_widen(so):
     assert err[16] < 1e-3 * total_move and err[16] < 1e-5
     assert err[8] < 0.1 * total_move
     assert err[16] < err[8] < err[4]
+
+
+def _wide_code_run(so, optimizer, p0, grads, eps, wd, beta1=0.9):
+    cfg = so.make_config(bits_m=16, bits_v=16, block_size=128, stochastic=0, beta1=beta1,
+                         quantile_p=0.0, eps=eps, weight_decay=wd, optimizer=optimizer)
+    p = p0.copy()
+    st = fresh_unpacked(so, p.size, cfg)
+    for t, g in enumerate(grads, 1):
+        so.step_unpacked(p, g, *st, t, cfg)
+    return p
+
+
+@pytest.mark.parametrize("which", ("AdamW", "Adam"))
+def test_wide_codes_follow_the_library_optimizers(so, which):
+    """16-bit codes against torch.optim.AdamW (decoupled decay) and torch.optim.Adam (decay added
+    to the gradient) run in binary64: the two differ visibly at this decay, and the oracle's
+    two modes follow the matching one."""
+    import torch
+    n, T, eps, wd = 1024, 25, 3e-4, 0.5
+    rng = np.random.default_rng(33)
+    p0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    grads = [(rng.standard_normal(n) * 1e-3).astype(np.float32) for _ in range(T)]
+    ref = {}
+    for name, cls in (("AdamW", torch.optim.AdamW), ("Adam", torch.optim.Adam)):
+        w = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+        opt = cls([w], lr=float(np.float32(1e-3)), betas=(float(np.float32(0.9)), float(np.float32(0.999))),
+                  eps=float(np.float32(eps)), weight_decay=float(np.float32(wd)))
+        for g in grads:
+            w.grad = torch.tensor(g, dtype=torch.float64)
+            opt.step()
+        ref[name] = w.detach().numpy()
+    got = _wide_code_run(so, so.ADAMW if which == "AdamW" else so.ADAM_L2, p0, grads, eps, wd)
+    other = "Adam" if which == "AdamW" else "AdamW"
+    move = np.max(np.abs(ref[which] - p0))
+    assert np.max(np.abs(got - ref[which])) < 2e-3 * move
+    assert np.max(np.abs(got - ref[other])) > 20 * np.max(np.abs(got - ref[which]))
+
+
+def test_adabelief_closed_forms(so):
+    """AdaBelief (the unsigned EMA follows (g - m^)^2 and gains eps at every step) in two cases
+    that have closed forms.  beta1 = 0: m^ = g, so s_t = eps (1 - beta2^t) / (1 - beta2) whatever
+    the gradients, every block is constant, and the update is lr g / (sqrt(eps / (1 - beta2)) + eps).
+    Constant gradient c: g - m^_t = c beta1^t, so s_t is a sum of two geometric series."""
+    n, T = 256, 10
+    rng = np.random.default_rng(8)
+    b2, lr, eps = float(np.float32(0.999)), float(np.float32(1e-3)), float(np.float32(1e-8))
+    # (1) beta1 = 0
+    cfg = so.make_config(bits_m=4, bits_v=3, block_size=128, beta1=0.0, weight_decay=0.0, eps=1e-8,
+                         optimizer=so.ADABELIEF)
+    p = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    p64 = p.astype(np.float64)
+    mc, ms, vc, vs, va = fresh_unpacked(so, n, cfg)
+    for t in range(1, T + 1):
+        g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        so.step_unpacked(p, g, mc, ms, vc, vs, va, t, cfg)
+        s_t = eps * (1 - b2 ** t) / (1 - b2)
+        assert np.allclose(vs, s_t, rtol=1e-5) and np.all(va == 1) and np.all(vc == 0)
+        p64 = p64 - lr * g.astype(np.float64) / (math.sqrt(eps / (1 - b2)) + eps)
+        assert np.allclose(p, p64, rtol=2e-6, atol=1e-9)
+    # (2) constant gradient, beta1 = 0.8: m^ sits on the top level, s is a constant block
+    b1, c = float(np.float32(0.8)), float(np.float32(2e-3))
+    cfg = so.make_config(bits_m=4, bits_v=3, block_size=128, beta1=0.8, weight_decay=0.0, eps=1e-8,
+                         optimizer=so.ADABELIEF)
+    p = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    p64 = p.astype(np.float64)
+    mc, ms, vc, vs, va = fresh_unpacked(so, n, cfg)
+    g = np.full(n, c, np.float32)
+    s = 0.0
+    for t in range(1, T + 1):
+        so.step_unpacked(p, g, mc, ms, vc, vs, va, t, cfg)
+        s = sum(b2 ** (t - k) * ((1 - b2) * (c * b1 ** k) ** 2 + eps) for k in range(1, t + 1))
+        assert np.allclose(vs, s, rtol=1e-5) and np.all(vc == 0)
+        assert np.allclose(ms, c * (1 - b1 ** t), rtol=1e-6)
+        p64 = p64 - lr * c / (math.sqrt(s / (1 - b2 ** t)) + eps)
+        assert np.allclose(p, p64, rtol=2e-6, atol=1e-9)
+
+
+def test_adabelief_follows_a_binary64_run_as_codes_widen(so):
+    """16-bit codes against AdaBelief with decoupled decay written out in binary64."""
+    n, T = 1024, 25
+    rng = np.random.default_rng(34)
+    p0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    grads = [(rng.standard_normal(n) * 1e-3).astype(np.float32) for _ in range(T)]
+    b1, b2, lr, wd, eps = (float(np.float32(x)) for x in (0.9, 0.999, 1e-3, 0.01, 1e-8))
+    p64, m, s = p0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t, g in enumerate(grads, 1):
+        g = g.astype(np.float64)
+        m = b1 * m + (1 - b1) * g
+        s = b2 * s + (1 - b2) * (g - m) ** 2 + eps
+        p64 = p64 * (1 - lr * wd) - lr * (m / (1 - b1 ** t)) / (np.sqrt(s / (1 - b2 ** t)) + eps)
+    got = _wide_code_run(so, so.ADABELIEF, p0, grads, 1e-8, 0.01)
+    adam = _wide_code_run(so, so.ADAMW, p0, grads, 1e-8, 0.01)
+    move = np.max(np.abs(p64 - p0))
+    assert np.max(np.abs(got - p64)) < 2e-3 * move
+    assert np.max(np.abs(adam - p64)) > 20 * np.max(np.abs(got - p64))
+
+
+def test_gradient_scale_is_one_multiplication_in_binary32(so):
+    """scale s on g equals scale 1 on fl(g * s), bit for bit; a power of two undoes exactly."""
+    n = 300
+    rng = np.random.default_rng(4)
+    g = (rng.standard_normal(n) * 3.0).astype(np.float32)
+    p0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    outs = []
+    for gg, s in ((g, 1 / 3), ((g * np.float32(1 / 3)).astype(np.float32), 1.0),
+                  (g * np.float32(4096), 1 / 3 / 4096)):
+        cfg = so.make_config(bits_m=2, bits_v=3, block_size=128, beta1=0.5, grad_scale=s)
+        p = p0.copy()
+        st = fresh_unpacked(so, n, cfg)
+        for t in (1, 2, 3):
+            so.step_unpacked(p, np.ascontiguousarray(gg, np.float32), *st, t, cfg)
+        outs.append((p, *st))
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert np.array_equal(a, b)
+
+
+def test_bf16_rounding_matches_the_library_conversion(so):
+    import torch
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(200000) * 10.0 ** rng.integers(-30, 30, 200000)).astype(np.float32)
+    x[:8] = [0.0, -0.0, 1.0, 3.39e38, 3.3895e38, -3.4e38, 1e-45, np.float32(1.00390625)]   # last: a tie
+    ties = (rng.integers(0, 0x7F7F, 1000).astype(np.uint32) << 16 | 0x8000).view(np.float32)
+    x = np.concatenate([x, ties, -ties])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(so.round_bf16(x), want)
 
 
 def test_swamping_thresholds_match_paper(so):
