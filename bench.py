@@ -141,6 +141,10 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps, copy the parameter buffer once (a plain copy of "
                          "known size that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--variant", default="adamw",
+                    choices=("adamw", "adam_l2", "adabelief", "adamw_mp", "adabelief_mp"),
+                    help="step variant: coupled decay, AdaBelief; *_mp adds the bf16 weight copy and "
+                         "a gradient scale read from device memory (the default, adamw, is the metric)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
@@ -159,18 +163,26 @@ def main():
                            solo.SOLO_GRAD_BF16 if w.grad_dtype == "bf16" else solo.SOLO_GRAD_FP32,
                            lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                            weight_decay=w.weight_decay, quantile_p=w.quantile_p, seed=synth.SEED_XI,
-                           flags=solo.SOLO_FLAG_STOCHASTIC | (solo.SOLO_FLAG_M_DYNAMIC_EXPONENT if w.m_codebook == "de" else 0))
+                           flags=solo.SOLO_FLAG_STOCHASTIC
+                           | (solo.SOLO_FLAG_M_DYNAMIC_EXPONENT if w.m_codebook == "de" else 0)
+                           | (solo.SOLO_FLAG_ADABELIEF if args.variant.startswith("adabelief") else 0)
+                           | (solo.SOLO_FLAG_COUPLED_DECAY if args.variant == "adam_l2" else 0))
+    mp = args.variant.endswith("_mp")
     gdtype = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
     p = device_params(torch, w, synth.SEED_PARAM)
     grads = [device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(w.config_id, k), gdtype)
              for k in (1, 2)]
     state = solo.SoloState(n, cfg)
+    extras = {}
+    if mp:
+        extras = {"param_bf16": torch.empty(n, dtype=torch.bfloat16, device="cuda"),
+                  "grad_scale": torch.tensor([0.5], dtype=torch.float32, device="cuda")}
     torch.cuda.synchronize()
 
     step = 0
     for _ in range(args.warmup):
         step += 1
-        state.step(p, grads[step & 1], step)
+        state.step(p, grads[step & 1], step, **extras)
     torch.cuda.synchronize()
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
@@ -178,7 +190,7 @@ def main():
     for k in range(args.steps):
         step += 1
         starts[k].record()                      # same stream as the launch (torch's current)
-        state.step(p, grads[step & 1], step)
+        state.step(p, grads[step & 1], step, **extras)
         ends[k].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -192,7 +204,7 @@ def main():
         del p_copy
 
     ms_per_step = wall / args.steps * 1e3
-    bpp = bytes_per_param(w)
+    bpp = bytes_per_param(w) + (2.0 if mp else 0.0)      # the bf16 copy is two more bytes written
     achieved = bpp * n / avg_kernel_s / 1e9
     out = {
         "metric": "updated_params_per_sec", "value": n / (wall / args.steps), "unit": "params/s",
@@ -201,14 +213,14 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "params": n, "bits_m": w.bits_m, "bits_v": w.bits_v,
                    "block_size": w.block_size, "grad_dtype": w.grad_dtype, "beta1": w.beta1,
-                   "m_codebook": w.m_codebook,
+                   "m_codebook": w.m_codebook, "variant": args.variant,
                    "bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name) if args.variant == "adamw" else None,
                      "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3,
                      "stream_probe": probe},
     }
-    del grads, p, state
+    del grads, p, state, extras
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_sample, n))

@@ -8,7 +8,8 @@
  *   dequantize both moments  ->  EMA update  ->  AdamW parameter update
  *   ->  per-block scale / quantile / log base  ->  re-quantize  ->  re-pack
  *
- *   1st moment  m : b_m-bit signed linear codes            (App. A, Eq. 1)
+ *   1st moment  m : b_m-bit signed linear codes, or the signed dynamic-
+ *                   exponent codes of the paper's own variants (App. A, Eq. 1)
  *   2nd moment  v : b_v-bit unsigned logarithmic codes, levels alpha^k,
  *                   log-domain stochastic rounding, per-block base alpha
  *                   from the p-quantile                     (Sec. 3.2.2)
@@ -63,8 +64,14 @@ enum { SOLO_GRAD_FP32 = 0, SOLO_GRAD_BF16 = 1 };
                                           App. A (the paper's own 4/2-bit and 2-bit AdamW, Sec. 3.4)
                                           instead of the signed linear ones */
 
+#define SOLO_FLAG_ADABELIEF 4u     /* AdaBelief instead of Adam (Sec. 4.2, "Generalizability"): the
+                                     unsigned EMA follows (g - m^)^2, m^ the fresh 1st moment, and
+                                     eps is added to that EMA itself at every step */
+#define SOLO_FLAG_COUPLED_DECAY 8u /* plain Adam: weight_decay * p is added to the gradient before
+                                     both EMAs and the parameter is not decayed separately */
+
 typedef struct solo_config {
-    uint32_t bits_m;       /* 2, 3 or 4: signed linear codes (App. A)                  */
+    uint32_t bits_m;       /* 2, 3 or 4: signed linear or dynamic-exponent codes (App. A) */
     uint32_t bits_v;       /* 2, 3 or 4: logarithmic codes (Sec. 3.2.2)                */
     uint32_t block_size;   /* 64 or 128 elements per block (Sec. 3.4 uses 128)         */
     uint32_t grad_dtype;   /* SOLO_GRAD_FP32 or SOLO_GRAD_BF16                         */
@@ -123,6 +130,22 @@ int solo_adamw_step(float *param, const void *grad,
                     uint32_t *v_codes, float *v_scale, float *v_base,
                     uint64_t n, uint64_t step,
                     const solo_config *cfg, void *stream);
+
+/* The same step with the two extras of a mixed-precision training loop (Sec. 1: 16-bit weights
+ * and gradients beside the 32-bit parameters) fused into the one pass:
+ *   param_bf16  bf16[n] DEVICE, 16-byte aligned, or NULL: receives every new parameter rounded
+ *               to bfloat16 (nearest, ties to even), so the 16-bit weights of the next forward
+ *               pass need no second sweep over the parameters
+ *   grad_scale  DEVICE pointer to one float, or NULL (= 1): every gradient is multiplied by it,
+ *               rounded to binary32, before anything else (reciprocal of the loss scale, a
+ *               clipping coefficient computed on the GPU); must be finite
+ * All other arguments, the return value and the state are those of solo_adamw_step, which is
+ * this call with both pointers NULL. */
+int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, const float *grad_scale,
+                       uint32_t *m_codes, float *m_scale,
+                       uint32_t *v_codes, float *v_scale, float *v_base,
+                       uint64_t n, uint64_t step,
+                       const solo_config *cfg, void *stream);
 
 /* Static, human-readable text for a return code. */
 const char *solo_strerror(int code);

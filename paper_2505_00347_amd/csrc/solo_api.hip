@@ -31,7 +31,9 @@ static bool config_ok(const solo_config *c)
     if (!(c->quantile_p >= 0.0f && c->quantile_p < 1.0f)) return false;
     if (!(c->eps >= 0.0f) || !isfinite(c->eps)) return false;
     if (!isfinite(c->lr) || !isfinite(c->weight_decay)) return false;
-    if ((c->flags & ~(SOLO_FLAG_STOCHASTIC | SOLO_FLAG_M_DYNAMIC_EXPONENT)) != 0 || c->reserved != 0) return false;
+    const uint32_t known = SOLO_FLAG_STOCHASTIC | SOLO_FLAG_M_DYNAMIC_EXPONENT | SOLO_FLAG_ADABELIEF |
+                           SOLO_FLAG_COUPLED_DECAY;
+    if ((c->flags & ~known) != 0 || c->reserved != 0) return false;
     if (c->index_offset % 8 != 0) return false;
     return true;
 }
@@ -145,8 +147,18 @@ int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_
                     uint32_t *v_codes, float *v_scale, float *v_base, uint64_t n, uint64_t step,
                     const solo_config *cfg, void *stream)
 {
+    return solo_adamw_step_mp(param, nullptr, grad, nullptr, m_codes, m_scale, v_codes, v_scale, v_base,
+                              n, step, cfg, stream);
+}
+
+int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, const float *grad_scale,
+                       uint32_t *m_codes, float *m_scale, uint32_t *v_codes, float *v_scale,
+                       float *v_base, uint64_t n, uint64_t step, const solo_config *cfg, void *stream)
+{
     if (!solo::config_ok(cfg) || step == 0) return SOLO_E_INVALID;
     if (n == 0) return SOLO_OK;
+    if ((param_bf16 && !solo::aligned(param_bf16, 16)) || (grad_scale && !solo::aligned(grad_scale, 4)))
+        return SOLO_E_INVALID;
     if (!solo::aligned(param, 16) || !solo::aligned(grad, 16) || !solo::aligned(m_codes, 16) ||
         !solo::aligned(v_codes, 16) || !solo::aligned(m_scale, 4) || !solo::aligned(v_scale, 4) ||
         !solo::aligned(v_base, 4))
@@ -166,7 +178,14 @@ int solo_adamw_step(float *param, const void *grad, uint32_t *m_codes, float *m_
     // bias corrections and the folded step scalars, in binary64 on the host
     const double bc1 = 1.0 - pow((double)cfg->beta1, (double)step);
     const double bc2 = 1.0 - pow((double)cfg->beta2, (double)step);
-    a.decay = (float)(1.0 - (double)cfg->lr * (double)cfg->weight_decay);
+    const bool coupled = (cfg->flags & SOLO_FLAG_COUPLED_DECAY) != 0;
+    const bool belief = (cfg->flags & SOLO_FLAG_ADABELIEF) != 0;
+    a.decay = coupled ? 1.0f : (float)(1.0 - (double)cfg->lr * (double)cfg->weight_decay);
+    a.l2 = coupled ? cfg->weight_decay : 0.0f;
+    a.belief = belief ? 1u : 0u;
+    a.eps_state = belief ? cfg->eps : 0.0f;
+    a.param_bf16 = param_bf16;
+    a.grad_scale = grad_scale;
     // p <- p * decay - m^ / (sqrt(v^) * denom_scale + denom_eps): the step size lr / bc1 is folded
     // into the denominator; a step size too small to divide by (|.| < 2^-100) means no update
     const double step_size = (double)cfg->lr / bc1;

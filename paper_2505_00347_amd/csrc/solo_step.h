@@ -79,6 +79,12 @@ struct StepArgs {
     uint32_t rank_full;     // rank of the quantile in a full block
     uint32_t key0, key1, key2;
     uint32_t stochastic;    // 0: xi = 0
+    // variants of the step (all uniform over the launch)
+    uint16_t *param_bf16;   // bf16 copy of the new parameters, written beside them (null: none)
+    const float *grad_scale;// device scalar every gradient is multiplied by first (null: 1)
+    float l2;               // Adam with coupled decay: weight_decay, g <- g + l2 * p; otherwise 0
+    float eps_state;        // AdaBelief: eps, added to the 2nd EMA itself at every step
+    uint32_t belief;        // AdaBelief: the 2nd EMA follows (g - m^)^2 instead of g^2
 };
 
 // ---------------------------------------------------------------- cross-lane
@@ -279,6 +285,17 @@ __device__ __forceinline__ void stream_store_f4(float *p, float4 x)
     __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p));
 }
 
+// Two binary32 values rounded to bfloat16 (nearest, ties to even: the hardware conversion),
+// the first in the low half.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+template <bool V> struct BoolTag { static constexpr bool value = V; };
+
 // Parameters and gradients of one lane and iteration as they come from memory.  In the
 // full-tile kernel the fp32 streams arrive in the coalesced layout (lane l holds elements
 // 4l..4l+3 and 256+4l..256+4l+3 of the 512-element chunk) and are transposed through LDS
@@ -325,7 +342,9 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL>
+// EXT: the instantiation that also serves the variants of the step (gradient scale, coupled
+// decay, AdaBelief, bf16 weight copy); the plain AdamW step runs the one without them.
+template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT>
 __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const StepArgs a)
 {
     constexpr int G = B / 8;                       // lanes per block
@@ -381,6 +400,7 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 
     // first parameters and gradients: in flight while the state image is staged
     RawPG raw = load_pg<BF16, TAIL>(a, tile_e0, lane);
+    const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;      // uniform: the gradient is transformed first
     // one pad vector after every 8 keeps both the coalesced (index = lane) and the per-lane
     // (index = 2 lane, 2 lane + 1) accesses of the transposition free of bank conflicts
     static_assert((kIter / 4 + kIter / 32) * 4 <= 64 * kColStride, "staging must fit the column area");
@@ -506,6 +526,10 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
                 g[4] = u2f(gb.x); g[5] = u2f(gb.y); g[6] = u2f(gb.z); g[7] = u2f(gb.w);
             }
         }
+        if (EXT) {                             // g <- fl(g * scale), then one fused g + l2 * p (l2 = 0: exact)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
+        }
         // next iteration's parameters and gradients, a whole iteration ahead of their use
         if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
         float mt[8], vt[8];
@@ -518,10 +542,18 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
         }
         float mh[8], vh[8];
         float m_absmax = 0.0f, v_max = 0.0f;
+        // AdaBelief without a branch: d = g - kb * m^ is g itself when kb = 0 and fl(g - m^) when
+        // kb = 1 (one rounding either way), and eps_state = 0 leaves v^ unchanged
+        const float kb = a.belief ? 1.0f : 0.0f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             mh[j] = __builtin_fmaf(a.beta1, mt[j], a.omb1 * g[j]);
-            vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (g[j] * g[j]));
+            if (EXT) {
+                const float d = __builtin_fmaf(-kb, mh[j], g[j]);
+                vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (d * d)) + a.eps_state;
+            } else {
+                vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (g[j] * g[j]));
+            }
             // parameter: decoupled decay, bias-corrected Adam direction
             // p <- p * decay - step_size * m^ / (sqrt(v^ / bc2) + eps), with step_size folded into the denominator
             const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
@@ -529,6 +561,17 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
             if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
             m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
             v_max = __builtin_fmaxf(v_max, vh[j]);
+        }
+        if (EXT && a.param_bf16) {                    // 16-bit copy of the new parameters, 16 bytes per lane
+            if (!TAIL) {
+                const u32x4_t h = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
+                                 pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+                __builtin_nontemporal_store(h, reinterpret_cast<u32x4_t *>(a.param_bf16 + e0));
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (ok[j]) a.param_bf16[e0 + j] = (uint16_t)pack_bf16(p[j], 0.0f);
+            }
         }
         if (!TAIL) {                           // back to the coalesced layout, streamed out
             wave_lds_sync();
@@ -708,14 +751,18 @@ hipError_t launch_step(uint32_t bits_v, uint32_t block_size, bool bf16, const St
 template <int BM, int BV, int B, bool BF16, bool MDE>
 hipError_t launch_one(const StepArgs &args, bool has_tail, hipStream_t stream)
 {
+    const bool ext = args.param_bf16 || args.grad_scale || args.belief || args.l2 != 0.0f;
     if (args.n_tiles_full) {
         const uint64_t grid = args.wg_per_xcd * kXcds;
-        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, false>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
+        if (ext)
+            hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, false, true>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
+        else
+            hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, false, false>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (has_tail) {
-        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true>), dim3(1), dim3(64), 0, stream, args);
+    if (has_tail) {                            // the ragged end: one wavefront, always the full-featured kernel
+        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true, true>), dim3(1), dim3(64), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

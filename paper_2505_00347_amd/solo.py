@@ -17,6 +17,8 @@ SOLO_OK, SOLO_E_INVALID, SOLO_E_UNSUPPORTED, SOLO_E_HIP = 0, -1, -2, -3
 SOLO_GRAD_FP32, SOLO_GRAD_BF16 = 0, 1
 SOLO_FLAG_STOCHASTIC = 1
 SOLO_FLAG_M_DYNAMIC_EXPONENT = 2
+SOLO_FLAG_ADABELIEF = 4
+SOLO_FLAG_COUPLED_DECAY = 8
 
 
 class solo_config(C.Structure):
@@ -66,12 +68,16 @@ def lib():
         L.solo_state_init.argtypes = [vp, vp, vp, vp, vp, u64, cfgp, vp]
         L.solo_adamw_step.restype = C.c_int
         L.solo_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, u64, cfgp, vp]
+        L.solo_adamw_step_mp.restype = C.c_int
+        L.solo_adamw_step_mp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, u64, cfgp, vp]
         _lib = L
     return _lib
 
 
 def _ptr(t):
     """Device pointer of a torch tensor (or a raw integer address)."""
+    if t is None:
+        return None
     return t if isinstance(t, int) else t.data_ptr()
 
 
@@ -108,6 +114,17 @@ def solo_adamw_step(param, grad, m_codes, m_scale, v_codes, v_scale, v_base, n, 
     return rc
 
 
+def solo_adamw_step_mp(param, param_bf16, grad, grad_scale, m_codes, m_scale, v_codes, v_scale,
+                       v_base, n, step, cfg, stream=None, check=True):
+    """param_bf16 (bf16 tensor) and grad_scale (one-element float32 device tensor) may be None."""
+    rc = lib().solo_adamw_step_mp(_ptr(param), _ptr(param_bf16), _ptr(grad), _ptr(grad_scale),
+                                  _ptr(m_codes), _ptr(m_scale), _ptr(v_codes), _ptr(v_scale),
+                                  _ptr(v_base), n, step, C.byref(cfg), _stream(stream) if n else None)
+    if check and rc != SOLO_OK:
+        raise SoloError(rc)
+    return rc
+
+
 class SoloState:
     """Device buffers of the packed optimizer state of n elements (caller-owned memory:
     plain torch tensors; int32 tensors carry the uint32 code words)."""
@@ -128,5 +145,8 @@ class SoloState:
     def buffers(self):
         return (self.m_codes, self.m_scale, self.v_codes, self.v_scale, self.v_base)
 
-    def step(self, param, grad, step, stream=None):
-        return solo_adamw_step(param, grad, *self.buffers(), self.n, step, self.cfg, stream)
+    def step(self, param, grad, step, stream=None, param_bf16=None, grad_scale=None):
+        if param_bf16 is None and grad_scale is None:
+            return solo_adamw_step(param, grad, *self.buffers(), self.n, step, self.cfg, stream)
+        return solo_adamw_step_mp(param, param_bf16, grad, grad_scale, *self.buffers(), self.n, step,
+                                  self.cfg, stream)

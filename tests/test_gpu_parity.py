@@ -47,10 +47,15 @@ def host_words(t):
 class GpuSide:
     """Device copy of (param, state) plus the C-ABI calls."""
 
-    def __init__(self, solo, n, cfg):
+    def __init__(self, solo, n, cfg, grad_scale=None, bf16_copy=False):
+        import torch
         self.solo, self.n, self.cfg = solo, n, cfg
         self.state = solo.SoloState(n, cfg)
         self.p = None
+        self.grad_scale = None if grad_scale is None else torch.tensor([grad_scale], dtype=torch.float32,
+                                                                       device="cuda")
+        # poisoned, so that an element the kernel skips shows
+        self.p_bf16 = torch.full((n,), float("nan"), dtype=torch.bfloat16, device="cuda") if bf16_copy else None
 
     def load(self, p, st):
         self.p = dev(p)
@@ -59,7 +64,16 @@ class GpuSide:
         s.m_scale.copy_(dev(st.m_scale)); s.v_scale.copy_(dev(st.v_scale)); s.v_base.copy_(dev(st.v_base))
 
     def step(self, g_dev, step):
-        self.state.step(self.p, g_dev, step)
+        self.state.step(self.p, g_dev, step, param_bf16=self.p_bf16, grad_scale=self.grad_scale)
+
+    def check_bf16_copy(self, so):
+        """The 16-bit copy is the kernel's own new parameter rounded to nearest-even, bit for bit."""
+        import torch
+        if self.p_bf16 is None:
+            return
+        torch.cuda.synchronize()
+        got = self.p_bf16.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, so.round_bf16(self.p.cpu().numpy())), "bf16 copy differs"
 
     def fetch(self):
         import torch
@@ -70,14 +84,17 @@ class GpuSide:
 
 
 def make_cfgs(so, solo, bm, bv, B, bf16=False, stochastic=1, beta1=None, p=0.1, seed=42, off=0,
-              lr=1e-3, wd=0.01, eps=1e-8, beta2=0.999, de=False):
+              lr=1e-3, wd=0.01, eps=1e-8, beta2=0.999, de=False, optimizer="adamw", grad_scale=None):
     beta1 = {2: 0.5, 3: 0.6, 4: 0.8}[bm] if beta1 is None else beta1
     oc = so.make_config(bits_m=bm, bits_v=bv, block_size=B, stochastic=stochastic, lr=lr, beta1=beta1,
                         beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p, seed=seed, index_offset=off,
-                        m_codebook=1 if de else 0)
+                        m_codebook=1 if de else 0,
+                        optimizer={"adamw": so.ADAMW, "adam_l2": so.ADAM_L2, "adabelief": so.ADABELIEF}[optimizer],
+                        grad_scale=1.0 if grad_scale is None else grad_scale)
     gc = solo.make_config(bits_m=bm, bits_v=bv, block_size=B, grad_dtype=1 if bf16 else 0, lr=lr,
                           beta1=beta1, beta2=beta2, eps=eps, weight_decay=wd, quantile_p=p,
-                          flags=(1 if stochastic else 0) | (2 if de else 0), seed=seed, index_offset=off)
+                          flags=(1 if stochastic else 0) | (2 if de else 0) |
+                          {"adamw": 0, "adam_l2": 8, "adabelief": 4}[optimizer], seed=seed, index_offset=off)
     return oc, gc
 
 
@@ -128,12 +145,12 @@ def grads_for(kind, n, std, seed, bf16):
 
 
 def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal", std=1e-3,
-                       seed0=100, **kw):
+                       seed0=100, bf16_copy=False, **kw):
     from paper_2505_00347_amd import synth
     oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
     p = synth.make_params(n)
     st = so.State(n, oc)
-    side = GpuSide(solo, n, gc)
+    side = GpuSide(solo, n, gc, kw.get("grad_scale"), bf16_copy)
     flips = 0
     for step in range(1, steps + 1):
         g, g_dev = grads_for(kind, n, std, seed0 + step, bf16)
@@ -141,16 +158,18 @@ def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal
         side.step(g_dev, step)
         margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
         flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
+        side.check_bf16_copy(so)
     assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
     return flips
 
 
-def run_free(so, solo, n, bm, bv, B, bf16=False, steps=10, kind="normal", std=1e-3, seed0=100, **kw):
+def run_free(so, solo, n, bm, bv, B, bf16=False, steps=10, kind="normal", std=1e-3, seed0=100,
+             bf16_copy=False, **kw):
     from paper_2505_00347_amd import synth
     oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
     p = synth.make_params(n)
     st = so.State(n, oc)
-    side = GpuSide(solo, n, gc)
+    side = GpuSide(solo, n, gc, kw.get("grad_scale"), bf16_copy)
     side.p = dev(p)
     got = side.fetch()                       # solo_state_init against the oracle's zero state
     assert np.array_equal(got[1], st.m_words) and np.array_equal(got[3], st.v_words)
@@ -161,7 +180,14 @@ def run_free(so, solo, n, bm, bv, B, bf16=False, steps=10, kind="normal", std=1e
         g, g_dev = grads_for(kind, n, std, seed0 + step, bf16)
         side.step(g_dev, step)
         margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
-        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-5, 1e-5 * oc.lr, tainted)
+        got = side.fetch()
+        flips += compare_step(so, oc, n, p, st, margin, got, 1e-5, 1e-5 * oc.lr, tainted)
+        side.check_bf16_copy(so)
+        if kw.get("optimizer") == "adam_l2":
+            # coupled decay feeds the parameter back into both EMAs: the last-bit differences of
+            # the two parameter updates would leak into the states, so the oracle continues from
+            # the kernel's parameters (the states stay free-running)
+            p[:] = got[0]
     assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
     assert tainted.mean() <= max(2.0 / tainted.size, 2 * FLIP_RATE * B * steps)
     return flips, int(tainted.sum())
@@ -237,6 +263,45 @@ def test_dynamic_exponent_all_formats(so, gpu, bm):
 def test_all_formats(so, gpu, bm, bv):
     for B, bf16, n in ((128, False, 3 * 2560 + 777), (64, True, 2 * 2560 + 1283)):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
+
+
+# ------------------------------------------------- variants of the step (one fused pass each)
+
+@pytest.mark.parametrize("optimizer", ("adamw", "adam_l2", "adabelief"))
+@pytest.mark.parametrize("bm,bv,B,bf16,de", [(2, 3, 128, True, False), (4, 2, 128, True, True),
+                                             (3, 3, 64, False, False), (4, 4, 128, False, False)])
+def test_step_variants(so, gpu, optimizer, bm, bv, B, bf16, de):
+    """Coupled decay, AdaBelief, a gradient scale read from device memory and the bf16 weight
+    copy, together, over several super-tiles and a ragged tail."""
+    n = 5 * 2560 + 1234
+    kw = dict(optimizer=optimizer, grad_scale=1.0 / 1024, wd=0.1, de=de, bf16_copy=True,
+              eps=1e-12 if optimizer == "adabelief" else 1e-8, std=1.024)
+    run_teacher_forced(so, gpu, n, bm, bv, B, bf16, steps=3, **kw)
+    run_free(so, gpu, n, bm, bv, B, bf16, steps=10, **kw)
+
+
+def test_bf16_copy_alone_and_scale_alone(so, gpu):
+    n = 3 * 2560 + 77
+    run_teacher_forced(so, gpu, n, 2, 3, 128, True, steps=2, bf16_copy=True)
+    run_teacher_forced(so, gpu, n, 2, 3, 128, True, steps=2, grad_scale=0.37, std=3e-3)
+    run_teacher_forced(so, gpu, n, 4, 4, 64, False, steps=2, grad_scale=1.0, optimizer="adabelief")
+
+
+def test_variants_reject_misaligned_extras(gpu):
+    import torch
+    n = 2560
+    cfg = gpu.make_config(bits_m=2, bits_v=3)
+    st = gpu.SoloState(n, cfg)
+    p = torch.zeros(n, device="cuda")
+    g = torch.zeros(n, device="cuda")
+    h = torch.zeros(n + 8, dtype=torch.bfloat16, device="cuda")
+    s = torch.ones(4, device="cuda")
+    bad_h = h.data_ptr() + 2
+    bad_s = s.data_ptr() + 2
+    assert gpu.solo_adamw_step_mp(p, bad_h, g, None, *st.buffers(), n, 1, cfg, check=False) == gpu.SOLO_E_INVALID
+    assert gpu.solo_adamw_step_mp(p, None, g, bad_s, *st.buffers(), n, 1, cfg, check=False) == gpu.SOLO_E_INVALID
+    assert gpu.solo_adamw_step_mp(p, h, g, s, *st.buffers(), n, 1, cfg, check=False) == gpu.SOLO_OK
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("n", (1, 7, 8, 9, 63, 64, 65, 127, 128, 129, 641, 2559, 2560, 2561, 5120, 7681))
@@ -321,7 +386,7 @@ def test_empty_and_invalid_arguments(gpu):
     assert solo.solo_adamw_step(0, g, *st.buffers(), 2560, 1, cfg, check=False) == solo.SOLO_E_INVALID
     for field, value in (("bits_m", 5), ("bits_v", 1), ("block_size", 96), ("grad_dtype", 2),
                          ("beta1", 1.0), ("beta2", -0.1), ("quantile_p", 1.0), ("eps", -1.0),
-                         ("flags", 4), ("reserved", 1), ("index_offset", 4), ("lr", float("nan"))):
+                         ("flags", 16), ("reserved", 1), ("index_offset", 4), ("lr", float("nan"))):
         bad = solo.make_config(2, 3, 128, 1)
         setattr(bad, field, value)
         assert solo.solo_adamw_step(*args, 2560, 1, bad, check=False) == solo.SOLO_E_INVALID, field
