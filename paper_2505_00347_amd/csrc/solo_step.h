@@ -252,6 +252,49 @@ struct DeLevels {
     }
 };
 
+// Rounding to the DE levels by one table look-up.  |z| <= 1 is cut into buckets by the top of
+// its binary32 pattern (the exponent and two fraction bits); the buckets are narrow enough that
+// none holds more than one rounding boundary, so a bucket knows the two neighbouring codes its
+// values can take.  One 8-byte entry per bucket and sign, { t, base }: the code is
+// base + (z > t).  For z >= 0, t is the boundary and base the code at or below it.  For z < 0
+// the code falls as |z| grows, so base is the code beyond the boundary and t = -nextup(boundary):
+// z > t exactly when |z| <= boundary.  Buckets without a boundary (and the negative buckets
+// beyond the last negative level) have t = +inf.  Entry 0 also serves every smaller magnitude.
+template <int BM>
+struct DeBuckets {
+    static constexpr int L = DeLevels<BM>::L;
+    static constexpr uint32_t bucket(float x) { return (__builtin_bit_cast(uint32_t, x) >> 21) & 0x3FFu; }
+    static constexpr uint32_t kLo = bucket(DeLevels<BM>::tab.mid[0]) - 1u;
+    static constexpr uint32_t kHi = bucket(1.0f);       // |z| can reach 1 + 2^-23
+    static constexpr int N = (int)(kHi - kLo) + 1;
+    struct Table {
+        uint32_t w[2 * N][2];
+        bool one_boundary_per_bucket;
+        constexpr Table() : w(), one_boundary_per_bucket(true)
+        {
+            constexpr uint32_t kInf = 0x7F800000u;
+            for (int b = 0; b < N; ++b) {
+                int below = 0, inside = 0;              // boundaries in lower buckets / in this one
+                uint32_t thr = kInf;
+                for (int k = 0; k <= L; ++k) {
+                    const uint32_t bk = bucket(DeLevels<BM>::tab.mid[k]);
+                    if (bk < kLo + (uint32_t)b) ++below;
+                    if (bk == kLo + (uint32_t)b) { ++inside; thr = __builtin_bit_cast(uint32_t, DeLevels<BM>::tab.mid[k]); }
+                }
+                if (inside > 1) one_boundary_per_bucket = false;
+                const int j0 = below, j1 = below + inside;
+                w[2 * b][0] = thr;                                       // z >= 0
+                w[2 * b][1] = (uint32_t)(L + j0);
+                const int n0 = L - (j0 < L ? j0 : L), n1 = L - (j1 < L ? j1 : L);   // z < 0: no level -1
+                w[2 * b + 1][0] = n0 != n1 ? ((thr + 1u) | 0x80000000u) : kInf;
+                w[2 * b + 1][1] = (uint32_t)n1;
+            }
+        }
+    };
+    static constexpr Table tab = Table();
+    static_assert(tab.one_boundary_per_bucket, "two fraction bits must separate the boundaries");
+};
+
 // ------------------------------------------------------------------- kernel
 
 // LDS accessed through 32-bit byte addresses, so that a table index can be
@@ -269,6 +312,8 @@ __device__ __forceinline__ uint32_t lds_u32(uint32_t addr) { return *(lds_u32_t 
 // wavefront's chunk, non-temporal (nothing of p or g is touched twice).
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) u32x2_t lds_u32x2_t;
 __device__ __forceinline__ float4 stream_load_f4(const float *p)
 {
     const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
@@ -374,9 +419,18 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     constexpr int kOffTv = ((kOffImgV + VW + 4 + 15) / 16) * 16;      // 64-byte aligned
     constexpr int kOffTm = kOffTv + ((NG * VT + 15) / 16) * 16;
     constexpr int kOffSc = kOffTm + NG * MTS;
+    constexpr bool kDeTable = MDE && BM >= 3;     // DE rounding by bucket table (two boundaries: compares are cheaper)
     constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16;
     static_assert(kSlab >= 64 * kColStride + 136, "column slack");
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * kSlab];
+    // the one thing the wavefronts of a workgroup share: the constant DE bucket table
+    constexpr int kDeWords = kDeTable ? 4 * DeBuckets<BM>::N : 16;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
+    if (kDeTable) {
+        const uint32_t *src = &DeBuckets<BM>::tab.w[0][0];
+        for (uint32_t w = threadIdx.x; w < (uint32_t)kDeWords; w += blockDim.x) lds_de[w] = src[w];
+        __syncthreads();                           // before any wavefront leaves
+    }
 
     const uint32_t lane = threadIdx.x & 63u;
     // the wavefront index is uniform: keeping it (and every address derived from the tile) in
@@ -447,9 +501,11 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 
     // DE codebook: the levels of the table entries this lane fills (entries lig, lig + G)
     float de_level[(16 + G - 1) / G];
+    uint32_t de_base = 0;                              // bucket table address, less the first bucket's index
     if (MDE) {
 #pragma unroll
         for (int r = 0; r < (MT + G - 1) / G; ++r) de_level[r] = DeLevels<BM>::level(lig + r * G);
+        if (kDeTable) de_base = lds_addr(lds_de) - 16u * DeBuckets<BM>::kLo;
     }
 
 #pragma unroll 1
@@ -677,10 +733,21 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
                 // DE: nearest level on the magnitude; inv_s = 1/Delta_m.  j = #midpoints below |z|
                 const float z = mh[j] * inv_s;
                 const float az = __builtin_fabsf(z);
-                uint32_t cnt = 0;
+                uint32_t code;
+                if (kDeTable) {
+                    // entry of the bucket of |z| (16 bytes per bucket: z >= 0, then z < 0)
+                    // (clamped on both sides: a non-finite input must not leave the table)
+                    const uint32_t bk = umin(umax(__builtin_amdgcn_ubfe(f2u(z), 21u, 10u), DeBuckets<BM>::kLo),
+                                             DeBuckets<BM>::kHi);
+                    const uint32_t addr = ((f2u(z) >> 28) & 8u) | ((bk << 4) + de_base);
+                    const u32x2_t e = *(lds_u32x2_t *)(uintptr_t)addr;
+                    code = e.y + (z > u2f(e.x) ? 1u : 0u);
+                } else {
+                    uint32_t cnt = 0;
 #pragma unroll
-                for (int k = 0; k <= L; ++k) cnt += (az > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
-                uint32_t code = (z < 0.0f) ? (uint32_t)L - umin(cnt, (uint32_t)L) : (uint32_t)L + cnt;
+                    for (int k = 0; k <= L; ++k) cnt += (az > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
+                    code = (z < 0.0f) ? (uint32_t)L - umin(cnt, (uint32_t)L) : (uint32_t)L + cnt;
+                }
                 if (TAIL && !ok[j]) code = 0;
                 m8_de |= code << (BM * j);
             }
