@@ -11,13 +11,13 @@ namespace solo {
 
 template <int BM, bool MDE>
 hipError_t launch_step(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
-                       bool has_tail, hipStream_t stream);
-template <> hipError_t launch_step<2, false>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<3, false>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<4, false>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<2, true>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<3, true>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
-template <> hipError_t launch_step<4, true>(uint32_t, uint32_t, bool, const StepArgs &, bool, hipStream_t);
+                       hipStream_t stream);
+template <> hipError_t launch_step<2, false>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_step<3, false>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_step<4, false>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_step<2, true>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_step<3, true>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_step<4, true>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
 
 static bool bits_ok(uint32_t b) { return b >= 2 && b <= 4; }
 
@@ -170,8 +170,7 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
     a.m_words = m_codes; a.m_scale = m_scale;
     a.v_words = v_codes; a.v_scale = v_scale; a.v_base = v_base;
     a.n = n;
-    a.n_tiles_full = n / solo::kTile;
-    a.wg_per_xcd = ((a.n_tiles_full + solo::kWaves - 1) / solo::kWaves + solo::kXcds - 1) / solo::kXcds;
+    a.n_tiles_full = 0; a.wg_per_xcd = 0;      // set by the launcher of the instantiation (its tile size)
     a.index_offset = cfg->index_offset;
     a.beta1 = cfg->beta1; a.omb1 = 1.0f - cfg->beta1;
     a.beta2 = cfg->beta2; a.omb2 = 1.0f - cfg->beta2;
@@ -208,18 +207,17 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
     a.key0 = (uint32_t)ka; a.key1 = (uint32_t)(ka >> 32); a.key2 = (uint32_t)kb;
     a.stochastic = (cfg->flags & SOLO_FLAG_STOCHASTIC) ? 1u : 0u;
 
-    const bool has_tail = (n % solo::kTile) != 0;
     const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;
     const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (cfg->bits_m) {
-    case 2: e = mde ? solo::launch_step<2, true>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s)
-                    : solo::launch_step<2, false>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s); break;
-    case 3: e = mde ? solo::launch_step<3, true>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s)
-                    : solo::launch_step<3, false>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s); break;
-    case 4: e = mde ? solo::launch_step<4, true>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s)
-                    : solo::launch_step<4, false>(cfg->bits_v, cfg->block_size, bf16, a, has_tail, s); break;
+    case 2: e = mde ? solo::launch_step<2, true>(cfg->bits_v, cfg->block_size, bf16, a, s)
+                    : solo::launch_step<2, false>(cfg->bits_v, cfg->block_size, bf16, a, s); break;
+    case 3: e = mde ? solo::launch_step<3, true>(cfg->bits_v, cfg->block_size, bf16, a, s)
+                    : solo::launch_step<3, false>(cfg->bits_v, cfg->block_size, bf16, a, s); break;
+    case 4: e = mde ? solo::launch_step<4, true>(cfg->bits_v, cfg->block_size, bf16, a, s)
+                    : solo::launch_step<4, false>(cfg->bits_v, cfg->block_size, bf16, a, s); break;
     default: return SOLO_E_UNSUPPORTED;
     }
     return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;

@@ -45,9 +45,9 @@
 
 namespace solo {
 
-constexpr int kTile = 2560;        // elements per wavefront super-tile
+constexpr int kTileUnit = 2560;    // lcm of the block sizes and of 16, 10 and 8 codes per word
 constexpr int kIter = 512;         // elements per iteration (64 lanes x 8)
-constexpr int kIters = kTile / kIter;
+constexpr int kLdsPerCu = 160 * 1024;
 #ifndef SOLO_WAVES
 #define SOLO_WAVES 4
 #endif
@@ -387,6 +387,43 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// LDS of one wavefront, one contiguous slab of 32-bit words (all offsets are compile-time
+// constants, so the sub-arrays are reached with instruction offsets from very few address
+// registers):
+//   columns   64 x 12 words  per-lane sorted keys + sentinel; doubles as the staging area of
+//                            the layout transposition at the start of an iteration
+//   img_m/v   the super-tile's code words (loaded once, updated in place, written back once)
+//   tv, tm    level tables of the blocks of the current iteration
+//   sc        3 block scalars (Delta_m, Delta_v, alpha) per block of the super-tile
+template <int BM, int BV, int B, bool MDE, int TILE>
+struct SlabLayout {
+    static constexpr int NG = 64 / (B / 8);
+    static constexpr int NBT = TILE / B;
+    static constexpr int MW = TILE / (32 / BM), VW = TILE / (32 / BV);
+    static constexpr int VT = 1 << BV;
+    static constexpr int MTS = 16;
+    static constexpr int kOffCol = 0;
+    static constexpr int kOffImgM = 64 * kColStride;
+    static constexpr int kOffImgV = kOffImgM + ((MW + 4 + 3) / 4) * 4;
+    static constexpr int kOffTv = ((kOffImgV + VW + 4 + 15) / 16) * 16;      // 64-byte aligned
+    static constexpr int kOffTm = kOffTv + ((NG * VT + 15) / 16) * 16;
+    static constexpr int kOffSc = kOffTm + NG * MTS;
+    static constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16;
+    static constexpr bool kDeTable = MDE && BM >= 3;     // DE rounding by bucket table (two boundaries: compares are cheaper)
+    static constexpr int kDeWords = kDeTable ? 4 * DeBuckets<BM>::N : 16;
+    static constexpr int kBytesPerWg = 4 * (kWaves * kSlab + kDeWords);
+};
+
+// Elements per wavefront super-tile: a longer tile spreads a wavefront's start-up (kernel
+// arguments, first loads) over more work, so the tile is doubled wherever the larger state
+// image still leaves room for SOLO_MIN_WAVES wavefronts per SIMD.
+template <int BM, int BV, int B, bool MDE>
+constexpr int tile_elems()
+{
+    constexpr int wgs = SOLO_MIN_WAVES * 4 / kWaves;              // workgroups per CU at that occupancy
+    return SlabLayout<BM, BV, B, MDE, 2 * kTileUnit>::kBytesPerWg * wgs <= kLdsPerCu ? 2 * kTileUnit : kTileUnit;
+}
+
 // EXT: the instantiation that also serves the variants of the step (gradient scale, coupled
 // decay, AdaBelief, bf16 weight copy); the plain AdamW step runs the one without them.
 template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT>
@@ -394,6 +431,9 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 {
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
+    constexpr int kTile = tile_elems<BM, BV, B, MDE>();   // elements of this wavefront's super-tile
+    constexpr int kIters = kTile / kIter;
+    using Lay = SlabLayout<BM, BV, B, MDE, kTile>;
     constexpr int NBT = kTile / B;                 // blocks per super-tile
     constexpr int L = (1 << (BM - 1)) - 1;
     constexpr int K = (1 << BV) - 1;
@@ -401,30 +441,18 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     constexpr int MW = kTile / CM, VW = kTile / CV; // words per super-tile
     constexpr int VT = K + 1;                      // entries of a block's v level table (4, 8, 16)
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1; // entries of a block's m level table (3, 7, 15; DE: 4, 8, 16)
-    constexpr int MTS = 16;                        // stride of the m tables
+    constexpr int MTS = Lay::MTS;                  // stride of the m tables
     constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
     constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;   // byte-index masks
 
-    // LDS of one wavefront, one contiguous slab (all offsets are compile-time constants, so the
-    // sub-arrays are reached with instruction offsets from very few address registers):
-    //   columns   64 x 12 words  per-lane sorted keys + sentinel; doubles as the staging area of
-    //                            the layout transposition at the start of an iteration
-    //   img_m/v   the super-tile's code words (loaded once, updated in place, written back once)
-    //   sc        3 x NBT block scalars (Delta_m, Delta_v, alpha), same life cycle
-    //   tv, tm    level tables of the NG blocks of the current iteration
     // A runaway column address (possible only with non-finite input) stays inside the slab.
-    constexpr int kOffCol = 0;
-    constexpr int kOffImgM = 64 * kColStride;
-    constexpr int kOffImgV = kOffImgM + ((MW + 4 + 3) / 4) * 4;
-    constexpr int kOffTv = ((kOffImgV + VW + 4 + 15) / 16) * 16;      // 64-byte aligned
-    constexpr int kOffTm = kOffTv + ((NG * VT + 15) / 16) * 16;
-    constexpr int kOffSc = kOffTm + NG * MTS;
-    constexpr bool kDeTable = MDE && BM >= 3;     // DE rounding by bucket table (two boundaries: compares are cheaper)
-    constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16;
+    constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
+    constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
+    constexpr bool kDeTable = Lay::kDeTable;
     static_assert(kSlab >= 64 * kColStride + 136, "column slack");
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * kSlab];
     // the one thing the wavefronts of a workgroup share: the constant DE bucket table
-    constexpr int kDeWords = kDeTable ? 4 * DeBuckets<BM>::N : 16;
+    constexpr int kDeWords = Lay::kDeWords;
     __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
     if (kDeTable) {
         const uint32_t *src = &DeBuckets<BM>::tab.w[0][0];
@@ -677,7 +705,36 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
                 head = lds_u32(haddr);
             }
         };
-        for (uint32_t k = 0; k < a.rank_full; ++k) extract_round(k);
+        if (!TAIL) {
+            // Full tiles: the pop is written out (run the holders under their own exec mask), so
+            // that a round is straight-line code with the loop's back edge as its only branch.
+            for (uint32_t k = 0; k < a.rank_full; ++k) {
+                const uint32_t mn = group_reduce<G>(head, UMin());
+                uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
+                if (__builtin_expect(__builtin_popcountll(holders) != NG, 0)) {
+                    uint64_t lowest = 0;           // a tie: the lowest holder of each group pops
+#pragma unroll
+                    for (int gi = 0; gi < NG; ++gi) {
+                        const uint64_t f = (holders >> (gi * G)) & (uint64_t)GMASK;
+                        lowest |= (f & (0 - f)) << (gi * G);
+                    }
+                    holders = lowest;
+                }
+                xp_bits = mn;
+                uint64_t saved;
+                asm volatile("s_mov_b64 %[saved], exec\n\t"
+                             "s_mov_b64 exec, %[holders]\n\t"
+                             "ds_read_b32 %[head], %[haddr] offset:4\n\t"
+                             "v_add_u32_e32 %[haddr], 4, %[haddr]\n\t"
+                             "s_mov_b64 exec, %[saved]\n\t"
+                             "s_waitcnt lgkmcnt(0)"
+                             : [head] "+v"(head), [haddr] "+v"(haddr), [saved] "=&s"(saved)
+                             : [holders] "s"(holders)
+                             : "memory");
+            }
+        } else {
+            for (uint32_t k = 0; k < a.rank_full; ++k) extract_round(k);
+        }
 
         // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
         const float num = (lane & 1u) ? (MDE ? 1.0f : (float)L) : u2f(xp_bits);
@@ -813,11 +870,16 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 // defined in solo_step_m{2,3,4}{,_de}.hip so that the families compile in parallel.
 template <int BM, bool MDE>
 hipError_t launch_step(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
-                       bool has_tail, hipStream_t stream);
+                       hipStream_t stream);
 
 template <int BM, int BV, int B, bool BF16, bool MDE>
-hipError_t launch_one(const StepArgs &args, bool has_tail, hipStream_t stream)
+hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
 {
+    StepArgs args = args_in;                   // the tiling belongs to the instantiation
+    constexpr int kTile = tile_elems<BM, BV, B, MDE>();
+    args.n_tiles_full = args.n / kTile;
+    args.wg_per_xcd = ((args.n_tiles_full + kWaves - 1) / kWaves + kXcds - 1) / kXcds;
+    const bool has_tail = (args.n % kTile) != 0;
     const bool ext = args.param_bf16 || args.grad_scale || args.belief || args.l2 != 0.0f;
     if (args.n_tiles_full) {
         const uint64_t grid = args.wg_per_xcd * kXcds;
@@ -838,12 +900,12 @@ hipError_t launch_one(const StepArgs &args, bool has_tail, hipStream_t stream)
 
 template <int BM, bool MDE>
 hipError_t launch_step_impl(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
-                            bool has_tail, hipStream_t stream)
+                            hipStream_t stream)
 {
 #define SOLO_CASE(BV_, B_)                                                             \
     if (bits_v == BV_ && block_size == B_)                                             \
-        return bf16 ? launch_one<BM, BV_, B_, true, MDE>(args, has_tail, stream)       \
-                    : launch_one<BM, BV_, B_, false, MDE>(args, has_tail, stream);
+        return bf16 ? launch_one<BM, BV_, B_, true, MDE>(args, stream)                 \
+                    : launch_one<BM, BV_, B_, false, MDE>(args, stream);
     SOLO_CASE(2, 64) SOLO_CASE(2, 128) SOLO_CASE(3, 64) SOLO_CASE(3, 128) SOLO_CASE(4, 64) SOLO_CASE(4, 128)
 #undef SOLO_CASE
     return hipErrorInvalidValue;

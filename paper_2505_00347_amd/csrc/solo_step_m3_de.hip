@@ -4,8 +4,8 @@
 namespace solo {
 template <>
 hipError_t launch_step<3, true>(uint32_t bits_v, uint32_t block_size, bool bf16, const StepArgs &args,
-                          bool has_tail, hipStream_t stream)
+                          hipStream_t stream)
 {
-    return launch_step_impl<3, true>(bits_v, block_size, bf16, args, has_tail, stream);
+    return launch_step_impl<3, true>(bits_v, block_size, bf16, args, stream);
 }
 }  // namespace solo

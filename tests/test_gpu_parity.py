@@ -17,6 +17,7 @@ import pytest
 
 pytestmark = pytest.mark.gpu
 
+TILE = 5120          # elements one wavefront of the step kernel owns (sizes below span several)
 FLIP_MARGIN = 5e-5
 FLIP_RATE = 1e-5
 
@@ -252,7 +253,7 @@ def test_paper_2bit_adamw_de_first_moment(so, gpu):
 
 @pytest.mark.parametrize("bm", (2, 3, 4))
 def test_dynamic_exponent_all_formats(so, gpu, bm):
-    for bv, B, bf16, n in ((3, 128, False, 3 * 2560 + 777), (4, 64, True, 2 * 2560 + 1283), (2, 64, False, 641)):
+    for bv, B, bf16, n in ((3, 128, False, 3 * TILE + 777), (4, 64, True, 2 * TILE + 1283), (2, 64, False, 641)):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=4, seed0=50 + bm, de=True)
 
 
@@ -261,7 +262,7 @@ def test_dynamic_exponent_all_formats(so, gpu, bm):
 @pytest.mark.parametrize("bm", (2, 3, 4))
 @pytest.mark.parametrize("bv", (2, 3, 4))
 def test_all_formats(so, gpu, bm, bv):
-    for B, bf16, n in ((128, False, 3 * 2560 + 777), (64, True, 2 * 2560 + 1283)):
+    for B, bf16, n in ((128, False, 3 * TILE + 777), (64, True, 2 * TILE + 1283)):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
 
 
@@ -273,7 +274,7 @@ def test_all_formats(so, gpu, bm, bv):
 def test_step_variants(so, gpu, optimizer, bm, bv, B, bf16, de):
     """Coupled decay, AdaBelief, a gradient scale read from device memory and the bf16 weight
     copy, together, over several super-tiles and a ragged tail."""
-    n = 5 * 2560 + 1234
+    n = 5 * TILE + 1234
     kw = dict(optimizer=optimizer, grad_scale=1.0 / 1024, wd=0.1, de=de, bf16_copy=True,
               eps=1e-12 if optimizer == "adabelief" else 1e-8, std=1.024)
     run_teacher_forced(so, gpu, n, bm, bv, B, bf16, steps=3, **kw)
@@ -281,7 +282,7 @@ def test_step_variants(so, gpu, optimizer, bm, bv, B, bf16, de):
 
 
 def test_bf16_copy_alone_and_scale_alone(so, gpu):
-    n = 3 * 2560 + 77
+    n = 3 * TILE + 77
     run_teacher_forced(so, gpu, n, 2, 3, 128, True, steps=2, bf16_copy=True)
     run_teacher_forced(so, gpu, n, 2, 3, 128, True, steps=2, grad_scale=0.37, std=3e-3)
     run_teacher_forced(so, gpu, n, 4, 4, 64, False, steps=2, grad_scale=1.0, optimizer="adabelief")
@@ -304,14 +305,14 @@ def test_variants_reject_misaligned_extras(gpu):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("n", (1, 7, 8, 9, 63, 64, 65, 127, 128, 129, 641, 2559, 2560, 2561, 5120, 7681))
+@pytest.mark.parametrize("n", (1, 7, 8, 9, 63, 64, 65, 127, 128, 129, 641, 2559, 2560, 2561, 5119, 5120, 5121, 7681, 10240, 15361))
 def test_ragged_sizes(so, gpu, n):
     run_free(so, gpu, n, 2, 3, 128, bf16=True, steps=3, std=1e-4, seed0=n)
     run_free(so, gpu, n, 3, 4, 64, steps=3, seed0=n + 1)
 
 
 def test_quantile_settings_and_nearest_rounding(so, gpu):
-    n = 4 * 2560 + 300
+    n = 4 * TILE + 300
     for p in (0.0, 0.05, 0.3, 0.5):
         run_teacher_forced(so, gpu, n, 4, 2, 128, steps=3, p=p, seed0=int(p * 100))
         run_teacher_forced(so, gpu, n, 2, 3, 64, steps=3, p=p, seed0=int(p * 100) + 1)
@@ -400,7 +401,7 @@ def test_empty_and_invalid_arguments(gpu):
 def test_runs_on_the_callers_stream(so, gpu):
     import torch
     from paper_2505_00347_amd import synth
-    n = 3 * 2560 + 100
+    n = 3 * TILE + 100
     oc, gc = make_cfgs(so, gpu, 4, 4, 128)
     p = synth.make_params(n)
     g = synth.make_grads(n, "normal", 1e-3, 5)
@@ -422,7 +423,7 @@ def test_runs_on_the_callers_stream(so, gpu):
 def test_full_size_7b_workload_sampled_tiles(so, gpu):
     """The LLaMA-7B-shaped workload exactly as bench.py launches it (6,738,415,616 elements,
     one call).  The oracle cannot run 6.7e9 elements in seconds, so the third step is checked
-    on sampled 2560-element super-tiles (first, last full, the ragged tail, tensor boundaries
+    on sampled 5120-element super-tiles (first, last full, the ragged tail, tensor boundaries
     and random ones): inputs of those slices are copied out before the step, the oracle runs
     on each slice with the slice's global offset, and every output byte of the slice is
     compared.  Properties that hold at any size are checked on the whole buffer."""
@@ -443,7 +444,7 @@ def test_full_size_7b_workload_sampled_tiles(so, gpu):
         state.step(p, g, step)
         del g
     g = bench.device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(5, 3), torch.bfloat16)
-    T = 2560
+    T = TILE
     n_tiles = n // T
     rng = np.random.default_rng(0)
     tiles = {0, 1, n_tiles - 1, n_tiles}                         # n_tiles = the ragged tail
