@@ -217,6 +217,8 @@ def main():
     res = cands[chosen]
     del cands, r
     torch.cuda.empty_cache()
+    if args.placements > 1:
+        res.run(trials)                          # back to a steady state after the idle gap of the frees
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
