@@ -420,30 +420,43 @@ def test_runs_on_the_callers_stream(so, gpu):
 
 # ---------------------------------- the benchmark's workload at its full size, sampled
 
-def test_full_size_7b_workload_sampled_tiles(so, gpu):
-    """The LLaMA-7B-shaped workload exactly as bench.py launches it (6,738,415,616 elements,
-    one call).  The oracle cannot run 6.7e9 elements in seconds, so the third step is checked
-    on sampled 5120-element super-tiles (first, last full, the ragged tail, tensor boundaries
-    and random ones): inputs of those slices are copied out before the step, the oracle runs
-    on each slice with the slice's global offset, and every output byte of the slice is
-    compared.  Properties that hold at any size are checked on the whole buffer."""
+@pytest.mark.parametrize("name,variant", [("c5_llama7b_2bit_3bit", "plain"), ("paper_4_2bit_llama7b", "mp")])
+def test_full_size_7b_workload_sampled_tiles(so, gpu, name, variant):
+    """The LLaMA-7B-shaped workloads exactly as bench.py launches them (6,738,415,616 elements,
+    one call): the metric's format, and the paper's own 4/2-bit format (dynamic-exponent m)
+    through solo_adamw_step_mp with the bf16 weight copy and a gradient scale.  The oracle cannot
+    run 6.7e9 elements in seconds, so the third step is checked on sampled 5120-element
+    super-tiles (first, last full, the ragged tail, tensor boundaries and random ones): inputs of
+    those slices are copied out before the step, the oracle runs on each slice with the slice's
+    global offset, and every output byte of the slice is compared.  Properties that hold at any
+    size are checked on the whole buffer."""
     import torch
     import bench
     from paper_2505_00347_amd import synth
     solo = gpu
     free, _ = torch.cuda.mem_get_info()
-    w = synth.workload("c5_llama7b_2bit_3bit")
+    w = synth.workload(name)
     n = w.n
-    if free < 60 * 2 ** 30:
-        pytest.skip("needs 60 GiB of free HBM")
-    oc, gc = make_cfgs(so, solo, w.bits_m, w.bits_v, w.block_size, bf16=True, beta1=w.beta1)
+    if free < 80 * 2 ** 30:
+        pytest.skip("needs 80 GiB of free HBM")
+    de = w.m_codebook == "de"
+    mp = variant == "mp"
+    scale = 0.25 if mp else None
+    oc, gc = make_cfgs(so, solo, w.bits_m, w.bits_v, w.block_size, bf16=True, beta1=w.beta1, de=de,
+                       grad_scale=scale, lr=w.lr)
+    cm, cv, B = 32 // w.bits_m, 32 // w.bits_v, w.block_size
     p = bench.device_params(torch, w, synth.SEED_PARAM)
     state = solo.SoloState(n, gc)
+    extras = {}
+    if mp:
+        extras = {"param_bf16": torch.full((n,), float("nan"), dtype=torch.bfloat16, device="cuda"),
+                  "grad_scale": torch.tensor([scale], dtype=torch.float32, device="cuda")}
+    gstd = w.grad_std / (scale or 1.0)
     for step in (1, 2):
-        g = bench.device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(5, step), torch.bfloat16)
-        state.step(p, g, step)
+        g = bench.device_grads(torch, n, w.grad_kind, gstd, synth.seed_grad(w.config_id, step), torch.bfloat16)
+        state.step(p, g, step, **extras)
         del g
-    g = bench.device_grads(torch, n, w.grad_kind, w.grad_std, synth.seed_grad(5, 3), torch.bfloat16)
+    g = bench.device_grads(torch, n, w.grad_kind, gstd, synth.seed_grad(w.config_id, 3), torch.bfloat16)
     T = TILE
     n_tiles = n // T
     rng = np.random.default_rng(0)
@@ -455,41 +468,47 @@ def test_full_size_7b_workload_sampled_tiles(so, gpu):
     tiles |= set(int(t) for t in rng.integers(0, n_tiles, 40))
     tiles = sorted(tiles)
 
+    def state_slices(a, st):
+        nb = st.m_scale.size
+        return (host_words(state.m_codes[a // cm:a // cm + st.m_words.size]),
+                state.m_scale[a // B:a // B + nb].cpu().numpy(),
+                host_words(state.v_codes[a // cv:a // cv + st.v_words.size]),
+                state.v_scale[a // B:a // B + nb].cpu().numpy(),
+                state.v_base[a // B:a // B + nb].cpu().numpy())
+
     def grab(t):
         a, b = t * T, min(n, (t + 1) * T)
         cnt = b - a
         st = so.State(cnt, oc)
-        st.m_words[:] = host_words(state.m_codes[a // 16:a // 16 + st.m_words.size])
-        st.v_words[:] = host_words(state.v_codes[a // 10:a // 10 + st.v_words.size])
-        nb = st.m_scale.size
-        st.m_scale[:] = state.m_scale[a // 128:a // 128 + nb].cpu().numpy()
-        st.v_scale[:] = state.v_scale[a // 128:a // 128 + nb].cpu().numpy()
-        st.v_base[:] = state.v_base[a // 128:a // 128 + nb].cpu().numpy()
+        st.m_words[:], st.m_scale[:], st.v_words[:], st.v_scale[:], st.v_base[:] = state_slices(a, st)
         return a, cnt, p[a:b].cpu().numpy(), g[a:b].float().cpu().numpy(), st
 
     before = [grab(t) for t in tiles]
     assert float(state.v_base.min()) > 0 and float(state.v_base.max()) <= 1
-    state.step(p, g, 3)
+    state.step(p, g, 3, **extras)
     torch.cuda.synchronize()
     flips = 0
     for a, cnt, p0, g0, st in before:
-        cfg_t = so.make_config(bits_m=2, bits_v=3, block_size=128, beta1=w.beta1, index_offset=a)
+        cfg_t = so.make_config(bits_m=w.bits_m, bits_v=w.bits_v, block_size=B, beta1=w.beta1, lr=w.lr,
+                               index_offset=a, m_codebook=1 if de else 0, grad_scale=scale or 1.0)
         margin = so.step_packed(p0, g0, st, 3, cfg_t, want_margin=True)
-        nb = st.m_scale.size
-        got = (p[a:a + cnt].cpu().numpy(),
-               host_words(state.m_codes[a // 16:a // 16 + st.m_words.size]),
-               state.m_scale[a // 128:a // 128 + nb].cpu().numpy(),
-               host_words(state.v_codes[a // 10:a // 10 + st.v_words.size]),
-               state.v_scale[a // 128:a // 128 + nb].cpu().numpy(),
-               state.v_base[a // 128:a // 128 + nb].cpu().numpy())
+        got = (p[a:a + cnt].cpu().numpy(),) + state_slices(a, st)
         flips += compare_step(so, oc, cnt, p0, st, margin, got, 1e-6, 2e-6 * oc.lr)
+        if mp:
+            h = extras["param_bf16"][a:a + cnt].view(torch.int16).cpu().numpy().view(np.uint16)
+            assert np.array_equal(h, so.round_bf16(got[0])), "bf16 copy differs"
     assert flips <= 2
     # whole-buffer properties: codes in range, pad bits zero, scales finite and ordered
-    vw = state.v_codes
-    assert int((vw >> 30).abs().max()) == 0                      # two pad bits of every 3-bit word
-    mw = state.m_codes
-    both = mw & (mw >> 1) & 0x55555555                           # a 2-bit field equal to 3 is never produced
-    assert int(both.abs().max()) == 0
+    vw, mw = state.v_codes, state.m_codes
+    if w.bits_v == 3:
+        assert int((vw >> 30).abs().max()) == 0                  # two pad bits of every 3-bit word
+    if w.bits_m == 2 and not de:
+        both = mw & (mw >> 1) & 0x55555555                       # a 2-bit field equal to 3 is never produced
+        assert int(both.abs().max()) == 0
     assert bool(torch.isfinite(state.m_scale).all()) and bool(torch.isfinite(state.v_scale).all())
-    assert float(state.v_base.min()) >= 2.0 ** (-64 / 7) * (1 - 1e-6) and float(state.v_base.max()) <= 1
+    K = 2 ** w.bits_v - 1
+    assert float(state.v_base.min()) >= 2.0 ** (-64 / K) * (1 - 1e-6) and float(state.v_base.max()) <= 1
     assert bool(torch.isfinite(p[:: 4099]).all())
+    if mp:
+        hb = extras["param_bf16"]
+        assert bool(torch.isfinite(hb[:: 4099]).all()) and bool(torch.isfinite(hb[-8192:]).all())
