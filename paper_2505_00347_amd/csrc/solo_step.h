@@ -69,6 +69,7 @@ struct StepArgs {
     float *v_base;
     uint64_t n;             // elements
     uint64_t n_tiles_full;  // super-tiles that lie entirely inside [0, n)
+    uint64_t tail_tile0;    // first 2560-element unit behind them (the ragged end: one wavefront per unit)
     uint64_t wg_per_xcd;    // workgroups per XCD: ceil(ceil(n_tiles_full / kWaves) / 8)
     uint64_t index_offset;  // global index of element 0 (multiple of 8)
     float beta1, omb1, beta2, omb2;
@@ -431,7 +432,8 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 {
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
-    constexpr int kTile = tile_elems<BM, BV, B, MDE>();   // elements of this wavefront's super-tile
+    // elements of this wavefront's super-tile; the ragged end is always cut into the small unit
+    constexpr int kTile = TAIL ? kTileUnit : tile_elems<BM, BV, B, MDE>();
     constexpr int kIters = kTile / kIter;
     using Lay = SlabLayout<BM, BV, B, MDE, kTile>;
     constexpr int NBT = kTile / B;                 // blocks per super-tile
@@ -468,8 +470,8 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     // group of super-tiles of XCD x's contiguous eighth of the buffer, so the wavefronts that
     // run at the same time on one XCD stream through one narrow address window.
     const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
-    const uint64_t tile = TAIL ? a.n_tiles_full : wg * kWaves + wave;
-    if (!TAIL && tile >= a.n_tiles_full) return;
+    const uint64_t tile = TAIL ? a.tail_tile0 + wave : wg * kWaves + wave;
+    if (TAIL ? tile * kTile >= a.n : tile >= a.n_tiles_full) return;
 
     const uint64_t nblk = (a.n + B - 1) / B;
     const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
@@ -880,6 +882,8 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
     args.n_tiles_full = args.n / kTile;
     args.wg_per_xcd = ((args.n_tiles_full + kWaves - 1) / kWaves + kXcds - 1) / kXcds;
     const bool has_tail = (args.n % kTile) != 0;
+    args.tail_tile0 = args.n_tiles_full * (kTile / kTileUnit);
+    const uint32_t tail_waves = (uint32_t)((args.n - args.tail_tile0 * kTileUnit + kTileUnit - 1) / kTileUnit);
     const bool ext = args.param_bf16 || args.grad_scale || args.belief || args.l2 != 0.0f;
     if (args.n_tiles_full) {
         const uint64_t grid = args.wg_per_xcd * kXcds;
@@ -890,8 +894,8 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (has_tail) {                            // the ragged end: one wavefront, always the full-featured kernel
-        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true, true>), dim3(1), dim3(64), 0, stream, args);
+    if (has_tail) {                            // the ragged end: one wavefront per 2560-element unit, always the full-featured kernel
+        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true, true>), dim3(1), dim3(64 * tail_waves), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
