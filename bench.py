@@ -145,6 +145,10 @@ def main():
                     choices=("adamw", "adam_l2", "adabelief", "adamw_mp", "adabelief_mp"),
                     help="step variant: coupled decay, AdaBelief; *_mp adds the bf16 weight copy and "
                          "a gradient scale read from device memory (the default, adamw, is the metric)")
+    ap.add_argument("--launch", default="flat", choices=("flat", "multi", "per_tensor"),
+                    help="flat: one call over the whole flat buffer (the metric); multi: the workload's "
+                         "tensors as separate buffers in one solo_adamw_step_multi launch; per_tensor: one "
+                         "solo_adamw_step call per tensor")
     ap.add_argument("--placements", type=int, default=3,
                     help="allocate the workload this many times and keep the allocation on which the "
                          "warm-up steps ran fastest (1: take the first allocation as it comes)")
@@ -181,13 +185,38 @@ def main():
             self.p = device_params(torch, w, synth.SEED_PARAM)
             self.grads = [device_grads(torch, n, w.grad_kind, w.grad_std,
                                        synth.seed_grad(w.config_id, k), gdtype) for k in (1, 2)]
-            self.state = solo.SoloState(n, cfg)
             self.extras = {}
             if mp:
                 self.extras = {"param_bf16": torch.empty(n, dtype=torch.bfloat16, device="cuda"),
                                "grad_scale": torch.tensor([0.5], dtype=torch.float32, device="cuda")}
             self.step = 0
+            if args.launch == "flat":
+                self.state = solo.SoloState(n, cfg)
+            else:
+                # every tensor of the workload with buffers of its own: slices of p and g (tensor
+                # sizes are multiples of 8, so the slices stay 16-byte aligned) and its own state
+                self.tensors, pos = [], 0
+                for _, numel, _ in w.tensors:
+                    assert numel % 8 == 0
+                    st = solo.SoloState(numel, cfg)
+                    h = self.extras["param_bf16"][pos:pos + numel] if mp else None
+                    self.tensors.append((self.p[pos:pos + numel], [g[pos:pos + numel] for g in self.grads], st, h))
+                    pos += numel
+                if args.launch == "multi":
+                    self.tables = [solo.SoloMultiTable([(t[0], t[1][k], t[2], t[3]) for t in self.tensors], cfg)
+                                   for k in (0, 1)]
             torch.cuda.synchronize()
+
+        def one_step(self):
+            self.step += 1
+            k = self.step & 1
+            if args.launch == "flat":
+                self.state.step(self.p, self.grads[k], self.step, **self.extras)
+            elif args.launch == "multi":
+                self.tables[k].step(self.step, grad_scale=self.extras.get("grad_scale"))
+            else:
+                for pt, gt, st, h in self.tensors:
+                    st.step(pt, gt[k], self.step, param_bf16=h, grad_scale=self.extras.get("grad_scale"))
 
         def run(self, count):
             """`count` steps; returns the HIP-event duration of each launch in ms (events on the
@@ -195,9 +224,8 @@ def main():
             starts = [torch.cuda.Event(enable_timing=True) for _ in range(count)]
             ends = [torch.cuda.Event(enable_timing=True) for _ in range(count)]
             for k in range(count):
-                self.step += 1
                 starts[k].record()
-                self.state.step(self.p, self.grads[self.step & 1], self.step, **self.extras)
+                self.one_step()
                 ends[k].record()
             torch.cuda.synchronize()
             return [s.elapsed_time(e) for s, e in zip(starts, ends)]
@@ -243,10 +271,11 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "params": n, "bits_m": w.bits_m, "bits_v": w.bits_v,
                    "block_size": w.block_size, "grad_dtype": w.grad_dtype, "beta1": w.beta1,
-                   "m_codebook": w.m_codebook, "variant": args.variant,
+                   "m_codebook": w.m_codebook, "variant": args.variant, "launch": args.launch,
+                   "tensors": len(w.tensors),
                    "bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name) if args.variant == "adamw" else None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name) if (args.variant, args.launch) == ("adamw", "flat") else None,
                      "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3,
                      "stream_probe": probe},
         "placement": {"candidates_ms": trial_ms, "chosen": chosen},

@@ -147,6 +147,59 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
                        uint64_t n, uint64_t step,
                        const solo_config *cfg, void *stream);
 
+/* ---- many tensors in one launch ------------------------------------------------------------
+ * A model is a set of tensors, each quantized on its own (Sec. 3.4: block-wise, small tensors
+ * included), and most of them are small: one launch per tensor is bound by launch latency.
+ * solo_adamw_step_multi runs the step of the same configuration over all tensors of a table in
+ * one launch.  The table is built on the host from `count` descriptors of DEVICE buffers and
+ * copied to device memory by the caller (who owns it, like every other buffer):
+ *
+ *   units = solo_multi_units(tensors, count, cfg);
+ *   bytes = solo_multi_table_bytes(count, units);
+ *   solo_multi_table_build(tensors, count, cfg, host_buffer, bytes, &table_flags);   // host -> host
+ *   copy host_buffer to a 16-byte aligned device buffer `table`
+ *   solo_adamw_step_multi(table, count, units, table_flags, grad_scale, step, cfg, stream);   // every step
+ *
+ * A tensor's buffers are laid out and aligned like those of solo_adamw_step (state sized by
+ * solo_code_words / solo_num_blocks for its own n); param_bf16 may be NULL per tensor; tensors
+ * with n == 0 are allowed.  Tensor k uses the xi stream of the flat step at
+ * index_offset = cfg->index_offset + sum over the tensors before it of n rounded up to a multiple
+ * of 2560, so its result is that of solo_adamw_step_mp on the tensor alone with that
+ * index_offset.  The table depends on the pointers, the sizes, cfg's state format (code widths,
+ * block size, codebook) and index_offset; it need not be rebuilt when only scalars of cfg or the
+ * step change. */
+typedef struct solo_tensor {
+    float *param;          /* fp32[n], read and written                      */
+    void *param_bf16;      /* bf16[n] or NULL: bf16 copy of the new parameters */
+    const void *grad;      /* fp32[n] or bf16[n] per cfg->grad_dtype          */
+    uint32_t *m_codes;
+    float *m_scale;
+    uint32_t *v_codes;
+    float *v_scale;
+    float *v_base;
+    uint64_t n;            /* elements                                       */
+} solo_tensor;
+
+/* Number of units the tensors are cut into for cfg's state format (a unit is the 2560 or 5120
+ * elements one wavefront of that format's kernel owns); 0 if cfg is invalid. */
+uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg);
+
+/* Bytes of the table for `count` tensors and `units` units. */
+size_t solo_multi_table_bytes(uint32_t count, uint64_t units);
+
+/* Fill `table_host` (HOST memory, table_bytes >= solo_multi_table_bytes) from `tensors` (HOST
+ * array of descriptors holding DEVICE pointers) and set *table_flags (SOLO_TABLE_*), which
+ * solo_adamw_step_multi takes back.  Checks every pointer's alignment. */
+#define SOLO_TABLE_BF16_COPY 1u   /* some tensor has a bf16 copy to write */
+int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const solo_config *cfg,
+                           void *table_host, size_t table_bytes, uint32_t *table_flags);
+
+/* One optimizer step over every tensor of `table_device` (DEVICE copy of a built table, 16-byte
+ * aligned; `count`, `units` and `table_flags` as at build time).  grad_scale as in solo_adamw_step_mp. */
+int solo_adamw_step_multi(const void *table_device, uint32_t count, uint64_t units,
+                          uint32_t table_flags, const float *grad_scale, uint64_t step,
+                          const solo_config *cfg, void *stream);
+
 /* Static, human-readable text for a return code. */
 const char *solo_strerror(int code);
 

@@ -19,6 +19,16 @@ template <> hipError_t launch_step<2, true>(uint32_t, uint32_t, bool, const Step
 template <> hipError_t launch_step<3, true>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
 template <> hipError_t launch_step<4, true>(uint32_t, uint32_t, bool, const StepArgs &, hipStream_t);
 
+template <int BM, bool MDE>
+hipError_t launch_multi(uint32_t bits_v, uint32_t block_size, bool bf16, const MultiArgs &args,
+                        hipStream_t stream);
+template <> hipError_t launch_multi<2, false>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
+template <> hipError_t launch_multi<3, false>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
+template <> hipError_t launch_multi<4, false>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
+template <> hipError_t launch_multi<2, true>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
+template <> hipError_t launch_multi<3, true>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
+template <> hipError_t launch_multi<4, true>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
+
 static bool bits_ok(uint32_t b) { return b >= 2 && b <= 4; }
 
 static bool config_ok(const solo_config *c)
@@ -70,6 +80,51 @@ static uint64_t mix64(uint64_t z)
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
+
+// The scalars of one step that do not depend on the buffer: momenta, the folded step size and
+// bias corrections (binary64 on the host), the rank of the quantile, the keys of the xi stream.
+static void step_scalars(StepArgs &a, const solo_config *cfg, uint64_t step)
+{
+    a.param = nullptr; a.grad = nullptr; a.m_words = nullptr; a.m_scale = nullptr;
+    a.v_words = nullptr; a.v_scale = nullptr; a.v_base = nullptr;
+    a.param_bf16 = nullptr; a.grad_scale = nullptr;
+    a.n = 0; a.index_offset = 0;
+    a.n_tiles_full = 0; a.wg_per_xcd = 0; a.tail_tile0 = 0;   // set by the launcher of the instantiation
+    a.beta1 = cfg->beta1; a.omb1 = 1.0f - cfg->beta1;
+    a.beta2 = cfg->beta2; a.omb2 = 1.0f - cfg->beta2;
+    const double bc1 = 1.0 - pow((double)cfg->beta1, (double)step);
+    const double bc2 = 1.0 - pow((double)cfg->beta2, (double)step);
+    const bool coupled = (cfg->flags & SOLO_FLAG_COUPLED_DECAY) != 0;
+    const bool belief = (cfg->flags & SOLO_FLAG_ADABELIEF) != 0;
+    a.decay = coupled ? 1.0f : (float)(1.0 - (double)cfg->lr * (double)cfg->weight_decay);
+    a.l2 = coupled ? cfg->weight_decay : 0.0f;
+    a.belief = belief ? 1u : 0u;
+    a.eps_state = belief ? cfg->eps : 0.0f;
+    // p <- p * decay - m^ / (sqrt(v^) * denom_scale + denom_eps): the step size lr / bc1 is folded
+    // into the denominator; a step size too small to divide by (|.| < 2^-100) means no update
+    const double step_size = (double)cfg->lr / bc1;
+    if (fabs(step_size) < 0x1p-100) {
+        a.denom_scale = 0.0f;
+        a.denom_eps = INFINITY;
+    } else {
+        a.denom_scale = (float)(1.0 / sqrt(bc2) / step_size);
+        a.denom_eps = (float)((double)cfg->eps / step_size);
+    }
+    a.quantile_p = cfg->quantile_p;
+    // r = max(1, ceil(p * B)) with the product in binary32
+    float x = ceilf(cfg->quantile_p * (float)cfg->block_size);
+    a.rank_full = x < 1.0f ? 1u : (uint32_t)x;
+    if (a.rank_full > cfg->block_size) a.rank_full = cfg->block_size;
+    // keys of this step's xi stream
+    const uint64_t gamma = 0x9E3779B97F4A7C15ull;
+    const uint64_t z = cfg->seed + gamma * step;
+    const uint64_t ka = mix64(z + gamma), kb = mix64(z + 2 * gamma);
+    a.key0 = (uint32_t)ka; a.key1 = (uint32_t)(ka >> 32); a.key2 = (uint32_t)kb;
+    a.stochastic = (cfg->flags & SOLO_FLAG_STOCHASTIC) ? 1u : 0u;
+}
+
+// Layout of a multi-tensor table: `count` entries, then one uint32 tensor index per unit.
+static size_t multi_map_offset(uint32_t count) { return (size_t)count * sizeof(TensorEntry); }
 
 }  // namespace solo
 
@@ -166,46 +221,14 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
     if (n > (1ull << 40)) return SOLO_E_UNSUPPORTED;
 
     solo::StepArgs a;
+    solo::step_scalars(a, cfg, step);
     a.param = param; a.grad = grad;
     a.m_words = m_codes; a.m_scale = m_scale;
     a.v_words = v_codes; a.v_scale = v_scale; a.v_base = v_base;
     a.n = n;
-    a.n_tiles_full = 0; a.wg_per_xcd = 0;      // set by the launcher of the instantiation (its tile size)
     a.index_offset = cfg->index_offset;
-    a.beta1 = cfg->beta1; a.omb1 = 1.0f - cfg->beta1;
-    a.beta2 = cfg->beta2; a.omb2 = 1.0f - cfg->beta2;
-    // bias corrections and the folded step scalars, in binary64 on the host
-    const double bc1 = 1.0 - pow((double)cfg->beta1, (double)step);
-    const double bc2 = 1.0 - pow((double)cfg->beta2, (double)step);
-    const bool coupled = (cfg->flags & SOLO_FLAG_COUPLED_DECAY) != 0;
-    const bool belief = (cfg->flags & SOLO_FLAG_ADABELIEF) != 0;
-    a.decay = coupled ? 1.0f : (float)(1.0 - (double)cfg->lr * (double)cfg->weight_decay);
-    a.l2 = coupled ? cfg->weight_decay : 0.0f;
-    a.belief = belief ? 1u : 0u;
-    a.eps_state = belief ? cfg->eps : 0.0f;
     a.param_bf16 = param_bf16;
     a.grad_scale = grad_scale;
-    // p <- p * decay - m^ / (sqrt(v^) * denom_scale + denom_eps): the step size lr / bc1 is folded
-    // into the denominator; a step size too small to divide by (|.| < 2^-100) means no update
-    const double step_size = (double)cfg->lr / bc1;
-    if (fabs(step_size) < 0x1p-100) {
-        a.denom_scale = 0.0f;
-        a.denom_eps = INFINITY;
-    } else {
-        a.denom_scale = (float)(1.0 / sqrt(bc2) / step_size);
-        a.denom_eps = (float)((double)cfg->eps / step_size);
-    }
-    a.quantile_p = cfg->quantile_p;
-    // r = max(1, ceil(p * B)) with the product in binary32
-    float x = ceilf(cfg->quantile_p * (float)cfg->block_size);
-    a.rank_full = x < 1.0f ? 1u : (uint32_t)x;
-    if (a.rank_full > cfg->block_size) a.rank_full = cfg->block_size;
-    // keys of this step's xi stream
-    const uint64_t gamma = 0x9E3779B97F4A7C15ull;
-    const uint64_t z = cfg->seed + gamma * step;
-    const uint64_t ka = solo::mix64(z + gamma), kb = solo::mix64(z + 2 * gamma);
-    a.key0 = (uint32_t)ka; a.key1 = (uint32_t)(ka >> 32); a.key2 = (uint32_t)kb;
-    a.stochastic = (cfg->flags & SOLO_FLAG_STOCHASTIC) ? 1u : 0u;
 
     const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;
     const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
@@ -218,6 +241,92 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
                     : solo::launch_step<3, false>(cfg->bits_v, cfg->block_size, bf16, a, s); break;
     case 4: e = mde ? solo::launch_step<4, true>(cfg->bits_v, cfg->block_size, bf16, a, s)
                     : solo::launch_step<4, false>(cfg->bits_v, cfg->block_size, bf16, a, s); break;
+    default: return SOLO_E_UNSUPPORTED;
+    }
+    return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;
+}
+
+uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg)
+{
+    if (!tensors || !solo::config_ok(cfg)) return 0;
+    const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
+                                                     (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
+    uint64_t units = 0;
+    for (uint32_t k = 0; k < count; ++k) units += (tensors[k].n + unit - 1) / unit;
+    return units;
+}
+
+size_t solo_multi_table_bytes(uint32_t count, uint64_t units)
+{
+    return solo::multi_map_offset(count) + (size_t)units * sizeof(uint32_t);
+}
+
+int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const solo_config *cfg,
+                           void *table_host, size_t table_bytes, uint32_t *table_flags)
+{
+    if (!solo::config_ok(cfg) || !tensors || !table_host || !table_flags || count == 0) return SOLO_E_INVALID;
+    const uint64_t units = solo_multi_units(tensors, count, cfg);
+    if (table_bytes < solo_multi_table_bytes(count, units)) return SOLO_E_INVALID;
+    if (units > (1ull << 31)) return SOLO_E_UNSUPPORTED;
+    const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
+                                                     (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
+    solo::TensorEntry *entries = static_cast<solo::TensorEntry *>(table_host);
+    uint32_t *map = reinterpret_cast<uint32_t *>(static_cast<char *>(table_host) + solo::multi_map_offset(count));
+    uint64_t unit0 = 0, xi_offset = cfg->index_offset;
+    uint32_t flags = 0;
+    for (uint32_t k = 0; k < count; ++k) {
+        const solo_tensor &t = tensors[k];
+        if (t.n > (1ull << 40)) return SOLO_E_UNSUPPORTED;
+        if (t.n != 0 && (!solo::aligned(t.param, 16) || !solo::aligned(t.grad, 16) ||
+                         !solo::aligned(t.m_codes, 16) || !solo::aligned(t.v_codes, 16) ||
+                         !solo::aligned(t.m_scale, 4) || !solo::aligned(t.v_scale, 4) ||
+                         !solo::aligned(t.v_base, 4) || (t.param_bf16 && !solo::aligned(t.param_bf16, 16))))
+            return SOLO_E_INVALID;
+        if (t.n != 0 && t.param_bf16) flags |= SOLO_TABLE_BF16_COPY;
+        solo::TensorEntry &e = entries[k];
+        e.param = t.param; e.param_bf16 = static_cast<uint16_t *>(t.param_bf16); e.grad = t.grad;
+        e.m_words = t.m_codes; e.m_scale = t.m_scale;
+        e.v_words = t.v_codes; e.v_scale = t.v_scale; e.v_base = t.v_base;
+        e.n = t.n; e.unit0 = unit0;
+        e.index_offset = xi_offset;
+        e.reserved = 0;
+        const uint64_t nu = (t.n + unit - 1) / unit;
+        for (uint64_t u = 0; u < nu; ++u) map[unit0 + u] = k;
+        unit0 += nu;
+        xi_offset += (t.n + solo::kTileUnit - 1) / solo::kTileUnit * (uint64_t)solo::kTileUnit;
+    }
+    *table_flags = flags;
+    return SOLO_OK;
+}
+
+int solo_adamw_step_multi(const void *table_device, uint32_t count, uint64_t units, uint32_t table_flags,
+                          const float *grad_scale, uint64_t step, const solo_config *cfg, void *stream)
+{
+    if (!solo::config_ok(cfg) || step == 0) return SOLO_E_INVALID;
+    if (units == 0) return SOLO_OK;
+    if (count == 0 || !solo::aligned(table_device, 16) || (grad_scale && !solo::aligned(grad_scale, 4)))
+        return SOLO_E_INVALID;
+    if (units > (1ull << 31)) return SOLO_E_UNSUPPORTED;
+    solo::MultiArgs ma;
+    solo::step_scalars(ma.common, cfg, step);
+    ma.common.grad_scale = grad_scale;
+    ma.entries = static_cast<const solo::TensorEntry *>(table_device);
+    ma.unit_map = reinterpret_cast<const uint32_t *>(static_cast<const char *>(table_device) +
+                                                     solo::multi_map_offset(count));
+    ma.total_units = units;
+    ma.any_bf16_copy = (table_flags & SOLO_TABLE_BF16_COPY) ? 1u : 0u;
+    ma.groups_per_xcd = ((units + solo::kWaves - 1) / solo::kWaves + solo::kXcds - 1) / solo::kXcds;
+    const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;
+    const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    switch (cfg->bits_m) {
+    case 2: e = mde ? solo::launch_multi<2, true>(cfg->bits_v, cfg->block_size, bf16, ma, s)
+                    : solo::launch_multi<2, false>(cfg->bits_v, cfg->block_size, bf16, ma, s); break;
+    case 3: e = mde ? solo::launch_multi<3, true>(cfg->bits_v, cfg->block_size, bf16, ma, s)
+                    : solo::launch_multi<3, false>(cfg->bits_v, cfg->block_size, bf16, ma, s); break;
+    case 4: e = mde ? solo::launch_multi<4, true>(cfg->bits_v, cfg->block_size, bf16, ma, s)
+                    : solo::launch_multi<4, false>(cfg->bits_v, cfg->block_size, bf16, ma, s); break;
     default: return SOLO_E_UNSUPPORTED;
     }
     return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;

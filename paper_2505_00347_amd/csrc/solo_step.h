@@ -88,6 +88,36 @@ struct StepArgs {
     uint32_t belief;        // AdaBelief: the 2nd EMA follows (g - m^)^2 instead of g^2
 };
 
+// One tensor of a multi-tensor launch, as the kernel reads it from the caller's table
+// (device memory; built on the host by solo_multi_table_build).
+struct TensorEntry {
+    float *param;
+    uint16_t *param_bf16;   // may be null
+    const void *grad;
+    uint32_t *m_words;
+    float *m_scale;
+    uint32_t *v_words;
+    float *v_scale;
+    float *v_base;
+    uint64_t n;             // elements of the tensor
+    uint64_t unit0;         // index of the tensor's first unit among all units of the table
+    uint64_t index_offset;  // global index of the tensor's element 0 in the xi stream
+    uint64_t reserved;
+};
+static_assert(sizeof(TensorEntry) == 96, "table layout");
+
+struct MultiArgs {
+    StepArgs common;              // the scalars of the step; pointers, n and index_offset come from the table
+    const TensorEntry *entries;
+    const uint32_t *unit_map;     // tensor index of every unit
+    uint64_t total_units;
+    uint64_t groups_per_xcd;      // groups of kWaves units per XCD
+    uint32_t any_bf16_copy;       // some tensor of the table has a bf16 copy to write
+};
+
+// Elements per unit of a multi-tensor table for a format: the super-tile size of its kernels.
+inline int unit_elems(uint32_t bits_m, uint32_t bits_v, uint32_t block_size, bool mde);
+
 // ---------------------------------------------------------------- cross-lane
 
 template <int CTRL>
@@ -425,15 +455,32 @@ constexpr int tile_elems()
     return SlabLayout<BM, BV, B, MDE, 2 * kTileUnit>::kBytesPerWg * wgs <= kLdsPerCu ? 2 * kTileUnit : kTileUnit;
 }
 
-// EXT: the instantiation that also serves the variants of the step (gradient scale, coupled
-// decay, AdaBelief, bf16 weight copy); the plain AdamW step runs the one without them.
-template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT>
-__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const StepArgs a)
+inline int unit_elems(uint32_t bits_m, uint32_t bits_v, uint32_t block_size, bool mde)
+{
+#define SOLO_U(BM_, BV_, B_)                                                                  \
+    if (bits_m == BM_ && bits_v == BV_ && block_size == B_)                                   \
+        return mde ? tile_elems<BM_, BV_, B_, true>() : tile_elems<BM_, BV_, B_, false>();
+#define SOLO_UB(BM_, BV_) SOLO_U(BM_, BV_, 64) SOLO_U(BM_, BV_, 128)
+    SOLO_UB(2, 2) SOLO_UB(2, 3) SOLO_UB(2, 4) SOLO_UB(3, 2) SOLO_UB(3, 3) SOLO_UB(3, 4)
+    SOLO_UB(4, 2) SOLO_UB(4, 3) SOLO_UB(4, 4)
+#undef SOLO_UB
+#undef SOLO_U
+    return 0;
+}
+
+// One super-tile of TILE elements, processed by the calling wavefront: the whole step for the
+// elements [tile * TILE, (tile + 1) * TILE) of the buffers in `a` (TAIL: clipped to a.n, with
+// bounds checks on every element).  `slab` is this wavefront's LDS, `lds_de` the workgroup's DE
+// bucket table.
+// EXT: the code that also serves the variants of the step (gradient scale, coupled decay,
+// AdaBelief, bf16 weight copy); the plain AdamW step runs the one without them.
+template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT, int TILE>
+__device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile, const uint32_t lane,
+                                          uint32_t *const slab, const uint32_t *const lds_de)
 {
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
-    // elements of this wavefront's super-tile; the ragged end is always cut into the small unit
-    constexpr int kTile = TAIL ? kTileUnit : tile_elems<BM, BV, B, MDE>();
+    constexpr int kTile = TILE;
     constexpr int kIters = kTile / kIter;
     using Lay = SlabLayout<BM, BV, B, MDE, kTile>;
     constexpr int NBT = kTile / B;                 // blocks per super-tile
@@ -452,32 +499,11 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
     constexpr bool kDeTable = Lay::kDeTable;
     static_assert(kSlab >= 64 * kColStride + 136, "column slack");
-    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * kSlab];
-    // the one thing the wavefronts of a workgroup share: the constant DE bucket table
-    constexpr int kDeWords = Lay::kDeWords;
-    __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
-    if (kDeTable) {
-        const uint32_t *src = &DeBuckets<BM>::tab.w[0][0];
-        for (uint32_t w = threadIdx.x; w < (uint32_t)kDeWords; w += blockDim.x) lds_de[w] = src[w];
-        __syncthreads();                           // before any wavefront leaves
-    }
-
-    const uint32_t lane = threadIdx.x & 63u;
-    // the wavefront index is uniform: keeping it (and every address derived from the tile) in
-    // scalar registers frees vector registers
-    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // Workgroup ids are dealt round-robin to the 8 XCDs; workgroup (x + 8 i) takes the i-th
-    // group of super-tiles of XCD x's contiguous eighth of the buffer, so the wavefronts that
-    // run at the same time on one XCD stream through one narrow address window.
-    const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
-    const uint64_t tile = TAIL ? a.tail_tile0 + wave : wg * kWaves + wave;
-    if (TAIL ? tile * kTile >= a.n : tile >= a.n_tiles_full) return;
 
     const uint64_t nblk = (a.n + B - 1) / B;
     const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
     const uint64_t tile_e0 = tile * kTile;
 
-    uint32_t *const slab = lds_slab + wave * kSlab;
     uint32_t *const img_m = slab + kOffImgM, *const img_v = slab + kOffImgV;
     float *const sc = reinterpret_cast<float *>(slab + kOffSc);
     uint32_t *const col = slab + kOffCol + lane * kColStride;
@@ -868,6 +894,74 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     }
 }
 
+// The DE bucket table of a workgroup: copied from constant memory once, before any wavefront
+// of the workgroup can leave.
+template <int BM, bool MDE, int WORDS>
+__device__ __forceinline__ void load_de_table(uint32_t *lds_de)
+{
+    if (MDE && BM >= 3) {
+        const uint32_t *src = &DeBuckets<BM>::tab.w[0][0];
+        for (uint32_t w = threadIdx.x; w < (uint32_t)WORDS; w += blockDim.x) lds_de[w] = src[w];
+        __syncthreads();
+    }
+}
+
+// The step over one flat buffer.  Full super-tiles: one workgroup per kWaves of them.  TAIL: the
+// ragged end, cut into 2560-element units, one wavefront each.
+template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT>
+__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const StepArgs a)
+{
+    constexpr int kTile = TAIL ? kTileUnit : tile_elems<BM, BV, B, MDE>();
+    using Lay = SlabLayout<BM, BV, B, MDE, kTile>;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * Lay::kSlab];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[Lay::kDeWords];
+    load_de_table<BM, MDE, Lay::kDeWords>(lds_de);
+
+    const uint32_t lane = threadIdx.x & 63u;
+    // the wavefront index is uniform: keeping it (and every address derived from the tile) in
+    // scalar registers frees vector registers
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // Workgroup ids are dealt round-robin to the 8 XCDs; workgroup (x + 8 i) takes the i-th
+    // group of super-tiles of XCD x's contiguous eighth of the buffer, so the wavefronts that
+    // run at the same time on one XCD stream through one narrow address window.
+    const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
+    const uint64_t tile = TAIL ? a.tail_tile0 + wave : wg * kWaves + wave;
+    if (TAIL ? tile * kTile >= a.n : tile >= a.n_tiles_full) return;
+    step_tile<BM, BV, B, BF16, MDE, TAIL, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
+}
+
+// The step over many tensors in one launch.  Every tensor is cut into units of the format's
+// super-tile size; one wavefront takes one unit, finds its tensor in the table (a scalar look-up) and runs the full-
+// tile code on a unit that lies inside the tensor and the bounds-checked code on a tensor's
+// ragged last unit.  Blocks never span tensors: each tensor is quantized on its own.
+template <int BM, int BV, int B, bool BF16, bool MDE, bool EXT>
+__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void multi_kernel(const MultiArgs ma)
+{
+    constexpr int kUnit = tile_elems<BM, BV, B, MDE>();
+    using Lay = SlabLayout<BM, BV, B, MDE, kUnit>;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * Lay::kSlab];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[Lay::kDeWords];
+    load_de_table<BM, MDE, Lay::kDeWords>(lds_de);
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * ma.groups_per_xcd + (blockIdx.x / kXcds);
+    const uint64_t unit = wg * kWaves + wave;
+    if (unit >= ma.total_units) return;
+    const TensorEntry &e = ma.entries[ma.unit_map[unit]];       // uniform: scalar loads
+    StepArgs a = ma.common;
+    a.param = e.param; a.param_bf16 = e.param_bf16; a.grad = e.grad;
+    a.m_words = e.m_words; a.m_scale = e.m_scale;
+    a.v_words = e.v_words; a.v_scale = e.v_scale; a.v_base = e.v_base;
+    a.n = e.n; a.index_offset = e.index_offset;
+    const uint64_t tile = unit - e.unit0;
+    uint32_t *const slab = lds_slab + wave * Lay::kSlab;
+    if ((tile + 1) * kUnit <= a.n)
+        step_tile<BM, BV, B, BF16, MDE, false, EXT, kUnit>(a, tile, lane, slab, lds_de);
+    else
+        step_tile<BM, BV, B, BF16, MDE, true, true, kUnit>(a, tile, lane, slab, lds_de);
+}
+
 // Host-side launcher of one instantiation family (fixed bits_m and 1st-moment codebook);
 // defined in solo_step_m{2,3,4}{,_de}.hip so that the families compile in parallel.
 template <int BM, bool MDE>
@@ -900,6 +994,33 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+template <int BM, bool MDE>
+hipError_t launch_multi(uint32_t bits_v, uint32_t block_size, bool bf16, const MultiArgs &args,
+                        hipStream_t stream);
+
+template <int BM, bool MDE>
+hipError_t launch_multi_impl(uint32_t bits_v, uint32_t block_size, bool bf16, const MultiArgs &args,
+                             hipStream_t stream)
+{
+    const uint64_t grid = args.groups_per_xcd * kXcds;
+    if (grid == 0 || grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const StepArgs &c = args.common;
+    const bool ext = args.any_bf16_copy || c.grad_scale || c.belief || c.l2 != 0.0f;
+#define SOLO_LAUNCH(BV_, B_, BF_, EXT_)                                                                 \
+    hipLaunchKernelGGL((multi_kernel<BM, BV_, B_, BF_, MDE, EXT_>), dim3((uint32_t)grid),               \
+                       dim3(kWaves * 64), 0, stream, args)
+#define SOLO_CASE(BV_, B_)                                                                              \
+    if (bits_v == BV_ && block_size == B_) {                                                            \
+        if (bf16) { if (ext) SOLO_LAUNCH(BV_, B_, true, true); else SOLO_LAUNCH(BV_, B_, true, false); } \
+        else      { if (ext) SOLO_LAUNCH(BV_, B_, false, true); else SOLO_LAUNCH(BV_, B_, false, false); } \
+        return hipGetLastError();                                                                       \
+    }
+    SOLO_CASE(2, 64) SOLO_CASE(2, 128) SOLO_CASE(3, 64) SOLO_CASE(3, 128) SOLO_CASE(4, 64) SOLO_CASE(4, 128)
+#undef SOLO_CASE
+#undef SOLO_LAUNCH
+    return hipErrorInvalidValue;
 }
 
 template <int BM, bool MDE>

@@ -8,4 +8,10 @@ hipError_t launch_step<2, true>(uint32_t bits_v, uint32_t block_size, bool bf16,
 {
     return launch_step_impl<2, true>(bits_v, block_size, bf16, args, stream);
 }
+template <>
+hipError_t launch_multi<2, true>(uint32_t bits_v, uint32_t block_size, bool bf16, const MultiArgs &args,
+                          hipStream_t stream)
+{
+    return launch_multi_impl<2, true>(bits_v, block_size, bf16, args, stream);
+}
 }  // namespace solo

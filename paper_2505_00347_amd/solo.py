@@ -39,6 +39,12 @@ def make_config(bits_m=4, bits_v=4, block_size=128, grad_dtype=SOLO_GRAD_FP32, l
                        weight_decay, quantile_p, flags, 0, seed, index_offset)
 
 
+class solo_tensor(C.Structure):
+    _fields_ = [("param", C.c_void_p), ("param_bf16", C.c_void_p), ("grad", C.c_void_p),
+                ("m_codes", C.c_void_p), ("m_scale", C.c_void_p), ("v_codes", C.c_void_p),
+                ("v_scale", C.c_void_p), ("v_base", C.c_void_p), ("n", C.c_uint64)]
+
+
 class SoloError(RuntimeError):
     def __init__(self, code):
         self.code = code
@@ -70,6 +76,13 @@ def lib():
         L.solo_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, u64, cfgp, vp]
         L.solo_adamw_step_mp.restype = C.c_int
         L.solo_adamw_step_mp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, u64, cfgp, vp]
+        tp = C.POINTER(solo_tensor)
+        L.solo_multi_units.restype = C.c_uint64; L.solo_multi_units.argtypes = [tp, u32, cfgp]
+        L.solo_multi_table_bytes.restype = C.c_size_t; L.solo_multi_table_bytes.argtypes = [u32, u64]
+        L.solo_multi_table_build.restype = C.c_int
+        L.solo_multi_table_build.argtypes = [tp, u32, cfgp, vp, C.c_size_t, C.POINTER(C.c_uint32)]
+        L.solo_adamw_step_multi.restype = C.c_int
+        L.solo_adamw_step_multi.argtypes = [vp, u32, u64, u32, vp, u64, cfgp, vp]
         _lib = L
     return _lib
 
@@ -123,6 +136,54 @@ def solo_adamw_step_mp(param, param_bf16, grad, grad_scale, m_codes, m_scale, v_
     if check and rc != SOLO_OK:
         raise SoloError(rc)
     return rc
+
+
+def solo_multi_units(tensors, count, cfg): return lib().solo_multi_units(tensors, count, C.byref(cfg))
+def solo_multi_table_bytes(count, units): return lib().solo_multi_table_bytes(count, units)
+
+
+def solo_multi_table_build(tensors, count, cfg, table_host, table_bytes, check=True):
+    """Returns (return code, table flags)."""
+    flags = C.c_uint32(0)
+    rc = lib().solo_multi_table_build(tensors, count, C.byref(cfg), table_host, table_bytes, C.byref(flags))
+    if check and rc != SOLO_OK:
+        raise SoloError(rc)
+    return rc, flags.value
+
+
+def solo_adamw_step_multi(table_device, count, units, table_flags, grad_scale, step, cfg, stream=None,
+                          check=True):
+    rc = lib().solo_adamw_step_multi(_ptr(table_device), count, units, table_flags, _ptr(grad_scale), step,
+                                     C.byref(cfg), _stream(stream) if units else None)
+    if check and rc != SOLO_OK:
+        raise SoloError(rc)
+    return rc
+
+
+class SoloMultiTable:
+    """The device table of a multi-tensor step, built from per-tensor (param, grad, SoloState[,
+    param_bf16]) tuples of torch tensors: marshals the descriptors, lets the library build the
+    table in host memory and copies it to the device."""
+
+    def __init__(self, items, cfg, device="cuda"):
+        import torch
+        self.cfg, self.count = cfg, len(items)
+        arr = (solo_tensor * self.count)()
+        for k, it in enumerate(items):
+            p, g, st = it[0], it[1], it[2]
+            h = it[3] if len(it) > 3 else None
+            arr[k] = solo_tensor(_ptr(p), _ptr(h), _ptr(g), _ptr(st.m_codes), _ptr(st.m_scale),
+                                 _ptr(st.v_codes), _ptr(st.v_scale), _ptr(st.v_base), st.n)
+        self.units = solo_multi_units(arr, self.count, cfg)
+        nbytes = solo_multi_table_bytes(self.count, self.units)
+        host = torch.empty((nbytes + 15) // 16 * 16, dtype=torch.uint8)
+        _, self.flags = solo_multi_table_build(arr, self.count, cfg, host.data_ptr(), nbytes)
+        self.table = host.to(device)
+        self._keep = items                         # the buffers the table points to
+
+    def step(self, step, grad_scale=None, stream=None):
+        return solo_adamw_step_multi(self.table, self.count, self.units, self.flags, grad_scale, step,
+                                     self.cfg, stream)
 
 
 class SoloState:

@@ -27,7 +27,8 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol(solo):
     names = declared_functions()
-    assert {"solo_adamw_step", "solo_adamw_step_mp", "solo_state_init", "solo_code_words", "solo_num_blocks",
+    assert {"solo_adamw_step", "solo_adamw_step_mp", "solo_adamw_step_multi", "solo_multi_units",
+            "solo_multi_table_bytes", "solo_multi_table_build", "solo_state_init", "solo_code_words", "solo_num_blocks",
             "solo_state_bytes", "solo_beta1_default", "solo_beta1_bound", "solo_strerror"} <= set(names)
     raw = ctypes.CDLL(solo.LIB_PATH)
     for name in names:

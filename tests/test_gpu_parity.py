@@ -418,6 +418,86 @@ def test_runs_on_the_callers_stream(so, gpu):
     compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
 
 
+# ------------------------------------------------------- many tensors in one launch
+
+@pytest.mark.parametrize("bm,bv,B,bf16,de,optimizer,extras", [(2, 3, 128, True, False, "adamw", False),
+                                                             (2, 3, 128, True, False, "adamw", True),
+                                                             (4, 2, 128, True, True, "adamw", True),
+                                                             (3, 3, 64, False, False, "adabelief", True),
+                                                             (4, 4, 128, False, False, "adam_l2", False)])
+def test_multi_tensor_step_equals_per_tensor_steps(so, gpu, bm, bv, B, bf16, de, optimizer, extras):
+    """solo_adamw_step_multi over tensors of awkward sizes (empty, smaller than a block, one
+    element past a unit, several units) against the oracle run on every tensor alone with the
+    tensor's own xi offset; three steps from equal states, with and without the bf16 copy and the
+    gradient scale."""
+    import torch
+    from paper_2505_00347_amd import synth
+    solo = gpu
+    sizes = [1, 127, 128, 0, 2559, 2560, 2561, 4096, 5000, 12800, 3 * 2560 + 1, 20017, 64]
+    off0 = 8 * 1000
+    scale = 0.5 if extras else 1.0
+    kw = dict(optimizer=optimizer, de=de, off=off0, grad_scale=scale, eps=1e-12 if optimizer == "adabelief" else 1e-8)
+    oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
+    sides, ps, sts, offs = [], [], [], []
+    unit0 = 0
+    for k, n in enumerate(sizes):
+        sides.append(GpuSide(solo, n, gc, None, extras))
+        ps.append(synth.make_params(n, stream=k))
+        cfg_k = so.make_config(bits_m=bm, bits_v=bv, block_size=B, beta1=oc.beta1, eps=oc.eps,
+                               index_offset=off0 + 2560 * unit0, m_codebook=1 if de else 0,
+                               optimizer=oc.optimizer, grad_scale=scale)
+        offs.append(cfg_k)
+        sts.append(so.State(n, cfg_k))
+        unit0 += -(-n // 2560)
+    gscale = torch.tensor([scale], dtype=torch.float32, device="cuda") if extras else None
+    flips = 0
+    for step in (1, 2, 3):
+        gs = []
+        for k, n in enumerate(sizes):
+            g, g_dev = grads_for("normal", n, 2e-3, 700 + 10 * step + k, bf16)
+            gs.append((g, g_dev))
+            sides[k].load(ps[k], sts[k])
+        items = [(sides[k].p, gs[k][1], sides[k].state, sides[k].p_bf16) for k in range(len(sizes))]
+        table = solo.SoloMultiTable(items, gc)
+        table.step(step, grad_scale=gscale)
+        for k, n in enumerate(sizes):
+            if n == 0:
+                continue
+            margin = so.step_packed(ps[k], gs[k][0], sts[k], step, offs[k], want_margin=True)
+            flips += compare_step(so, offs[k], n, ps[k], sts[k], margin, sides[k].fetch(), 1e-6, 2e-6 * oc.lr)
+            sides[k].check_bf16_copy(so)
+    assert flips <= 2
+
+
+def test_multi_tensor_table_rejects_bad_descriptors(gpu):
+    import ctypes as C
+    import torch
+    solo = gpu
+    cfg = solo.make_config(bits_m=2, bits_v=3)
+    n = 3000
+    st = solo.SoloState(n, cfg)
+    p = torch.zeros(n, device="cuda")
+    g = torch.zeros(n, device="cuda")
+    arr = (solo.solo_tensor * 1)()
+    arr[0] = solo.solo_tensor(p.data_ptr(), None, g.data_ptr(), st.m_codes.data_ptr(), st.m_scale.data_ptr(),
+                              st.v_codes.data_ptr(), st.v_scale.data_ptr(), st.v_base.data_ptr(), n)
+    units = solo.solo_multi_units(arr, 1, cfg)
+    assert units in (1, 2)                       # 3000 elements: one 5120- or two 2560-element units
+    nbytes = solo.solo_multi_table_bytes(1, units)
+    assert nbytes == 96 + 4 * units
+    buf = (C.c_uint8 * nbytes)()
+    assert solo.solo_multi_table_build(arr, 1, cfg, buf, nbytes, check=False) == (solo.SOLO_OK, 0)
+    assert solo.solo_multi_table_build(arr, 1, cfg, buf, nbytes - 1, check=False)[0] == solo.SOLO_E_INVALID
+    arr[0].param = p.data_ptr() + 4
+    assert solo.solo_multi_table_build(arr, 1, cfg, buf, nbytes, check=False)[0] == solo.SOLO_E_INVALID
+    arr[0].param = p.data_ptr()
+    arr[0].m_scale = None
+    assert solo.solo_multi_table_build(arr, 1, cfg, buf, nbytes, check=False)[0] == solo.SOLO_E_INVALID
+    assert solo.solo_adamw_step_multi(0, 1, 2, 0, None, 1, cfg, check=False) == solo.SOLO_E_INVALID
+    assert solo.solo_adamw_step_multi(0, 1, 0, 0, None, 1, cfg, check=False) == solo.SOLO_OK
+    assert solo.solo_adamw_step_multi(p.data_ptr(), 1, 2, 0, None, 0, cfg, check=False) == solo.SOLO_E_INVALID
+
+
 # ---------------------------------- the benchmark's workload at its full size, sampled
 
 @pytest.mark.parametrize("name,variant", [("c5_llama7b_2bit_3bit", "plain"), ("paper_4_2bit_llama7b", "mp")])
