@@ -383,6 +383,89 @@ void so_quant_v_block(const float *x, uint32_t nb, uint32_t bits, float p,
     }
 }
 
+/* ------------------------------------------- comparison quantizers for v */
+
+/* The unsigned level sets the paper compares against (App. A; used on the 2nd moment by earlier
+ * low-bit optimizers), each with nearest rounding (Eq. 1) and Delta = max x:
+ *   SO_U_LINEAR         {0, 1/(2^b-1), ..., 1}
+ *   SO_U_LINEAR_NOZERO  {1/2^b, 2/2^b, ..., 1}         (the variant that excludes the zero point)
+ *   SO_U_DE             unsigned dynamic exponent (so_de_levels with is_signed = 0)
+ * They exist for the swamping experiments (Sec. 3.2.1: Cor. 3.2 and the synthetic example); the
+ * optimizer step never uses them. */
+enum { SO_U_LINEAR = 1, SO_U_LINEAR_NOZERO = 2, SO_U_DE = 3 };
+
+/* Writes the 2^b increasing levels of one of the sets above; returns their number (0: unknown). */
+int so_unsigned_levels(uint32_t bits, int kind, double *out)
+{
+    const int n = 1 << bits;
+    if (bits < 1 || bits > 8) return 0;
+    if (kind == SO_U_LINEAR) {
+        for (int k = 0; k < n; ++k) out[k] = (double)k / (double)(n - 1);
+        return n;
+    }
+    if (kind == SO_U_LINEAR_NOZERO) {
+        for (int k = 0; k < n; ++k) out[k] = (double)(k + 1) / (double)n;
+        return n;
+    }
+    if (kind == SO_U_DE) return so_de_levels(bits, 0, out);
+    return 0;
+}
+
+/* Q-dagger of a comparison quantizer: x~ = fl(fl(y_q) * Delta). */
+float so_dequant_unsigned(uint32_t code, float scale, uint32_t bits, int kind)
+{
+    double lv[256];
+    so_unsigned_levels(bits, kind, lv);
+    return (float)lv[code] * scale;
+}
+
+/* Eq. 1 for a comparison quantizer: Delta = max x over the block, q = argmin_k |x/Delta - y_k|
+ * (ties to the lower level), the division in binary32. */
+void so_quant_unsigned_block(const float *x, uint32_t nb, uint32_t bits, int kind,
+                             uint16_t *codes, float *scale)
+{
+    double lv[256];
+    const int n = so_unsigned_levels(bits, kind, lv);
+    float d = 0.0f;
+    for (uint32_t i = 0; i < nb; ++i) d = fmaxf(d, x[i]);
+    *scale = d;
+    for (uint32_t i = 0; i < nb; ++i) {
+        const double r = d > 0.0f ? (double)(x[i] / d) : 0.0;
+        int best = 0;
+        for (int k = 1; k < n; ++k)
+            if (fabs(r - lv[k]) < fabs(r - lv[best])) best = k;
+        codes[i] = (uint16_t)best;
+    }
+}
+
+/* One step of the quantized unsigned EMA alone (Sec. 3.1, Eqs. 2-4 with the signal given):
+ * dequantize, x^ = fma(beta, x~, fl((1-beta) z)), quantize, block by block.  kind 0 is the
+ * paper's logarithmic quantizer (so_quant_v_block; base holds alpha per block), kinds 1..3 the
+ * comparison quantizers (base unused).  step and seed feed the xi stream of kind 0. */
+int so_unsigned_ema_step(uint16_t *codes, float *scale, float *base, const float *z, uint64_t n,
+                         uint32_t block, float beta, uint32_t bits, int kind, float p,
+                         uint32_t stochastic, uint64_t seed, uint64_t step)
+{
+    if (block == 0 || block > SO_MAX_BLOCK || kind < 0 || kind > SO_U_DE) return -1;
+    const float omb = 1.0f - beta;
+    uint32_t keys[4];
+    so_xi_keys(seed, step, keys);
+    for (uint64_t i0 = 0, blk = 0; i0 < n; i0 += block, ++blk) {
+        float xh[SO_MAX_BLOCK];
+        const uint32_t nb = (uint32_t)((n - i0) < block ? (n - i0) : block);
+        for (uint32_t k = 0; k < nb; ++k) {
+            const float xt = kind == 0 ? so_dequant_v(codes[i0 + k], scale[blk], base[blk], bits)
+                                       : so_dequant_unsigned(codes[i0 + k], scale[blk], bits, kind);
+            xh[k] = fmaf(beta, xt, omb * z[i0 + k]);
+        }
+        if (kind == 0)
+            so_quant_v_block(xh, nb, bits, p, stochastic, keys, i0, codes + i0, scale + blk, base + blk, NULL);
+        else
+            so_quant_unsigned_block(xh, nb, bits, kind, codes + i0, scale + blk);
+    }
+    return 0;
+}
+
 /* -------------------------------------------------------------- the step */
 
 /* One optimizer step over n elements with one code per uint16 (any width

@@ -113,6 +113,15 @@ def _declare(L):
                                  C.c_uint64, C.POINTER(Config), C.c_void_p, C.c_int]
     L.so_max_threads.restype = C.c_int; L.so_max_threads.argtypes = []
     L.so_round_bf16.restype = None; L.so_round_bf16.argtypes = [_f32p, _u16p, C.c_uint64]
+    L.so_unsigned_levels.restype = C.c_int
+    L.so_unsigned_levels.argtypes = [C.c_uint32, C.c_int, C.POINTER(C.c_double)]
+    L.so_dequant_unsigned.restype = C.c_float
+    L.so_dequant_unsigned.argtypes = [C.c_uint32, C.c_float, C.c_uint32, C.c_int]
+    L.so_quant_unsigned_block.restype = None
+    L.so_quant_unsigned_block.argtypes = [_f32p, C.c_uint32, C.c_uint32, C.c_int, _u16p, C.POINTER(C.c_float)]
+    L.so_unsigned_ema_step.restype = C.c_int
+    L.so_unsigned_ema_step.argtypes = [_u16p, _f32p, _f32p, _f32p, C.c_uint64, C.c_uint32, C.c_float,
+                                       C.c_uint32, C.c_int, C.c_float, C.c_uint32, C.c_uint64, C.c_uint64]
 
 
 # ------------------------------------------------------------ scalar helpers
@@ -193,6 +202,60 @@ def quant_v_block(x, bits, p=0.1, stochastic=1, seed=42, step=1, i0=0, want_marg
                            margin.ctypes.data if want_margin else None)
     out = (codes, np.float32(scale.value), np.float32(base.value))
     return out + (margin,) if want_margin else out
+
+
+U_LOG, U_LINEAR, U_LINEAR_NOZERO, U_DE = 0, 1, 2, 3
+
+
+def unsigned_levels(bits, kind):
+    out = (C.c_double * 256)()
+    n = lib().so_unsigned_levels(bits, kind, out)
+    return np.array(out[:n])
+
+
+def quant_unsigned_block(x, bits, kind):
+    x = np.ascontiguousarray(x, np.float32)
+    codes = np.zeros(x.size, np.uint16)
+    scale = C.c_float(0)
+    lib().so_quant_unsigned_block(x, x.size, bits, kind, codes, C.byref(scale))
+    return codes, np.float32(scale.value)
+
+
+def dequant_unsigned(codes, scale, bits, kind):
+    return np.array([lib().so_dequant_unsigned(int(c), float(scale), bits, kind) for c in codes], np.float32)
+
+
+class UnsignedEma:
+    """A quantized unsigned EMA on its own (no optimizer around it): codes, one scale (and for the
+    logarithmic quantizer one base) per block."""
+
+    def __init__(self, x0, block, bits, kind, p=0.1, stochastic=1, seed=42):
+        x0 = np.ascontiguousarray(x0, np.float32)
+        self.n, self.block, self.bits, self.kind = x0.size, block, bits, kind
+        self.p, self.stochastic, self.seed, self.t = p, stochastic, seed, 0
+        nblk = -(-self.n // block)
+        self.codes = np.zeros(self.n, np.uint16)
+        self.scale = np.zeros(nblk, np.float32)
+        self.base = np.ones(nblk, np.float32)
+        # quantize the initial state: an EMA step with beta = 0 from the zero state
+        self.step(x0, 0.0)
+
+    def step(self, z, beta):
+        self.t += 1
+        rc = lib().so_unsigned_ema_step(self.codes, self.scale, self.base, np.ascontiguousarray(z, np.float32),
+                                        self.n, self.block, beta, self.bits, self.kind, self.p,
+                                        self.stochastic, self.seed, self.t)
+        assert rc == 0
+
+    def values(self):
+        out = np.empty(self.n, np.float32)
+        for b in range(self.scale.size):
+            sl = slice(b * self.block, min(self.n, (b + 1) * self.block))
+            if self.kind == U_LOG:
+                out[sl] = [dequant_v(int(c), self.scale[b], self.base[b], self.bits) for c in self.codes[sl]]
+            else:
+                out[sl] = dequant_unsigned(self.codes[sl], self.scale[b], self.bits, self.kind)
+        return out
 
 
 def round_bf16(x):

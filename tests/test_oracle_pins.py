@@ -382,3 +382,100 @@ def test_de_quantizer_is_nearest_level(so, bits):
     mid = np.float32((levels[L + 1] + levels[L + 2]) / 2)
     codes, _ = so.quant_m_de_block(np.array([1.0, mid, -mid, np.nextafter(mid, np.float32(2))], np.float32), bits)
     assert list(codes) == [2 * L + 1, L + 1, L - 1, L + 2]
+
+
+# ------------------------------------------- comparison quantizers and signal swamping
+
+def test_unsigned_level_sets(so):
+    """App. A: unsigned linear {0, 1/(2^b-1), ..., 1}, the variant without the zero point
+    {1/2^b, ..., 1}, and the unsigned dynamic exponent set, whose radii Fact A.1 prints."""
+    for b in (2, 3, 4, 8):
+        n = 2 ** b
+        assert np.allclose(so.unsigned_levels(b, so.U_LINEAR), np.arange(n) / (n - 1), atol=1e-15)
+        assert np.allclose(so.unsigned_levels(b, so.U_LINEAR_NOZERO), np.arange(1, n + 1) / n, atol=1e-15)
+    for kind, bits, rmin, rmed, rmax in read_golden("de_radii.txt"):
+        if kind != "unsigned":
+            continue
+        lv = so.unsigned_levels(int(bits), so.U_DE)
+        radii = np.diff(lv) / 2
+        for want, got in ((rmin, radii.min()), (rmed, np.median(radii)), (rmax, radii.max())):
+            if want != "-":
+                assert abs(got - float(want)) < 6e-4, (bits, want, got)
+
+
+def test_comparison_quantizers_round_to_the_nearest_level(so):
+    rng = np.random.default_rng(5)
+    for kind in (so.U_LINEAR, so.U_LINEAR_NOZERO, so.U_DE):
+        for bits in (2, 3, 4):
+            x = rng.random(300).astype(np.float32)
+            x[7] = 1.0
+            codes, scale = so.quant_unsigned_block(x, bits, kind)
+            assert scale == 1.0
+            lv = so.unsigned_levels(bits, kind)
+            want = np.argmin(np.abs(x.astype(np.float64)[:, None] - lv[None, :]), axis=1)
+            assert np.array_equal(codes, want)
+            assert np.allclose(so.dequant_unsigned(codes, scale, bits, kind), lv[codes], rtol=1e-6)
+
+
+def swamped_levels(so, bits, kind, beta):
+    """Levels whose state keeps its code for the two extreme signals z = 0 and z = Delta (hence
+    for every signal in between), with Delta held at 1 by one element that keeps receiving 1."""
+    lv = so.unsigned_levels(bits, kind)
+    n = lv.size
+    stuck = np.ones(n, bool)
+    for z_val in (0.0, 1.0):
+        ema = so.UnsignedEma(np.concatenate([lv, [1.0]]).astype(np.float32), n + 1, bits, kind)
+        assert np.array_equal(ema.codes[:n], np.arange(n))
+        z = np.full(n + 1, z_val, np.float32)
+        z[n] = 1.0
+        ema.step(z, beta)
+        stuck &= ema.codes[:n] == np.arange(n)
+    return stuck
+
+
+def test_unsigned_swamping_thresholds_match_paper(so):
+    """Cor. 3.2: above the printed momentum every level of the linear set, and half of the
+    levels of the dynamic exponent set, swallow any signal z <= Delta.  For the linear set the
+    bound is tight (the top level with z = 0 moves a little below it); for the dynamic exponent
+    set it is only sufficient (it bounds |z - y| by Delta), so the converse is checked far below.
+    (8-bit is printed to three digits where the threshold moves in the fourth.)"""
+    for kind, bits, beta in read_golden("swamping_thresholds_unsigned.txt"):
+        bits, beta = int(bits), float(beta)
+        k = so.U_LINEAR if kind == "linear" else so.U_DE
+        n = 2 ** bits
+        need = n if kind == "linear" else n // 2
+        slack = 0.0015 if bits == 8 else 0.001
+        assert swamped_levels(so, bits, k, beta + slack).sum() >= need, (kind, bits)
+        below = (beta - (0.002 if bits == 8 else 0.02)) if kind == "linear" else 0.5
+        assert swamped_levels(so, bits, k, below).sum() < need, (kind, bits)
+
+
+def test_synthetic_uniform_signals_swamp_linear_and_de_but_not_the_log_quantizer(so):
+    """The synthetic example of Sec. 3.2.1: 1000 states quantized as one tensor, states and
+    signals from U[0, 1], beta = 0.99.  The exact EMA pulls every element to 0.5; the 3- and 4-bit
+    linear and dynamic exponent states never leave their first codes, the paper's logarithmic
+    quantizer with stochastic rounding follows."""
+    rng = np.random.default_rng(0)
+    n, T, beta = 1000, 300, 0.99
+    x0 = rng.random(n).astype(np.float32)
+    Z = [rng.random(n).astype(np.float32) for _ in range(T)]
+    exact = x0.astype(np.float64)
+    for z in Z:
+        exact = beta * exact + (1 - beta) * z
+    assert exact.std() < 0.06                       # the exact EMA has contracted towards 0.5
+    res = {}
+    for bits in (3, 4):
+        for kind in (so.U_LINEAR, so.U_LINEAR_NOZERO, so.U_DE, so.U_LOG):
+            ema = so.UnsignedEma(x0, n, bits, kind)
+            first = ema.codes.copy()
+            for z in Z:
+                ema.step(z, beta)
+            v = ema.values().astype(np.float64)
+            res[bits, kind] = (np.mean(ema.codes == first), np.sqrt(np.mean((v - exact) ** 2)), v.std())
+    for bits in (3, 4):
+        for kind in (so.U_LINEAR, so.U_LINEAR_NOZERO, so.U_DE):
+            unchanged, rms, std = res[bits, kind]
+            assert unchanged > 0.97 and std > 0.25 and rms > 0.2, (bits, kind, res[bits, kind])
+        unchanged, rms, std = res[bits, so.U_LOG]
+        assert unchanged < 0.3 and rms < 0.5 * res[bits, so.U_LINEAR][1], (bits, res[bits, so.U_LOG])
+    assert res[4, so.U_LOG][1] < res[3, so.U_LOG][1]

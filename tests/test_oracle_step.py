@@ -75,7 +75,7 @@ def brute_step(so, p, g, mc, ms, vc, vs, va, step, cfg):
             out_vs[blk], out_va[blk] = 0, 1
             out_vc[sl] = 0
             continue
-        r = max(1, math.ceil(float(np.float32(cfg.quantile_p)) * nb - 1e-9))
+        r = max(1, math.ceil(float(np.float32(cfg.quantile_p) * np.float32(nb))))   # product in binary32
         rho = max(np.sort(vh)[r - 1] / dv, 2.0 ** -64)
         alpha = rho ** (1.0 / K)
         out_va[blk] = alpha
@@ -95,11 +95,12 @@ def brute_step(so, p, g, mc, ms, vc, vs, va, step, cfg):
 
 
 @pytest.mark.parametrize("bm,bv,B", [(2, 2, 64), (2, 3, 128), (3, 3, 128), (4, 4, 128),
-                                     (4, 2, 64), (3, 4, 64), (2, 4, 128), (4, 3, 128), (3, 2, 64)])
+                                     (4, 2, 64), (3, 4, 64), (2, 4, 128), (4, 3, 128), (3, 2, 64),
+                                     (4, 2, 2048), (2, 2, 2048)])       # 2048: the large block of Sec. 4.2
 @pytest.mark.parametrize("codebook", (0, 1))
 def test_step_against_brute_force_on_tiny_tensors(so, bm, bv, B, codebook):
     rng = np.random.default_rng(1000 + 16 * bm + bv)
-    for n in (B, 2 * B + 17, 256, 5):
+    for n in ((B, 2 * B + 17, 256, 5) if B < 2048 else (B + 300,)):
         cfg = so.make_config(bits_m=bm, bits_v=bv, block_size=B, beta1=0.5 if bm == 2 else 0.8,
                              seed=9, index_offset=8 * 123456789, m_codebook=codebook)
         p = (rng.standard_normal(n) * 0.02).astype(np.float32)
