@@ -168,7 +168,11 @@ def main():
     n = w.n
     cfg = solo.make_config(w.bits_m, w.bits_v, w.block_size,
                            solo.SOLO_GRAD_BF16 if w.grad_dtype == "bf16" else solo.SOLO_GRAD_FP32,
-                           lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                           lr=w.lr, beta1=w.beta1, beta2=w.beta2,
+                           # AdaBelief adds eps to the 2nd EMA itself; its published default is 1e-16
+                           # (1e-8 would swamp the squared residuals of these gradients and make
+                           # every block constant)
+                           eps=1e-16 if args.variant.startswith("adabelief") else w.eps,
                            weight_decay=w.weight_decay, quantile_p=w.quantile_p, seed=synth.SEED_XI,
                            flags=solo.SOLO_FLAG_STOCHASTIC
                            | (solo.SOLO_FLAG_M_DYNAMIC_EXPONENT if w.m_codebook == "de" else 0)
