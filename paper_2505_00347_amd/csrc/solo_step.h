@@ -1,13 +1,19 @@
 // Device code of the fused SOLO AdamW step for gfx950 (wave64).
 //
-// Work decomposition.  The flat buffer is cut into super-tiles of 2560
-// elements (a multiple of every block size and of 16, 10 and 8 codes per
-// word, so a super-tile owns whole blocks and whole code words).  One
-// wavefront owns one super-tile and walks it in five iterations of 512
-// elements; a lane owns 8 consecutive elements per iteration, so a block of
-// 128 (64) elements is held by 16 (8) neighbouring lanes, i.e. one DPP row
-// (half row), and every per-block reduction is a few DPP steps.  Nothing is
-// shared between wavefronts: there is no workgroup barrier in the kernel.
+// Work decomposition.  A buffer is cut into super-tiles of 2560 or 5120
+// elements (2560 is a multiple of every block size and of 16, 10 and 8 codes
+// per word, so a super-tile owns whole blocks and whole code words; the
+// larger size is used wherever the LDS image of the tile's state still lets
+// five workgroups share a CU).  One wavefront owns one super-tile and walks
+// it in iterations of 512 elements; a lane owns 8 consecutive elements per
+// iteration, so a block of 128 (64) elements is held by 16 (8) neighbouring
+// lanes, i.e. one DPP row (half row), and every per-block reduction is a few
+// DPP steps.  Nothing is shared between wavefronts but a constant table: the
+// only workgroup barrier sits before the first tile is touched.
+//
+// step_tile() is the whole step for one super-tile; step_kernel runs it over
+// a flat buffer (full tiles, and the ragged end with bounds checks),
+// multi_kernel over the tensors of a caller-built table.
 //
 // The kernel is bound by vector-ALU issue as much as by HBM (packed FP32 is
 // off, so a CU retires 64 lane-operations per clock: about 80 per parameter at
