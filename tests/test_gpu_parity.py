@@ -418,6 +418,49 @@ def test_runs_on_the_callers_stream(so, gpu):
     compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
 
 
+def test_step_can_be_captured_in_a_hip_graph(so, gpu):
+    """The library allocates nothing, synchronises nothing and enqueues only kernels, so a step
+    can be recorded into a HIP graph.  The replayed step (same step number, inputs restored by
+    eager copies between the replays) must reproduce the eager step bit for bit, every time."""
+    import torch
+    from paper_2505_00347_amd import synth
+    solo = gpu
+    n = 3 * TILE + 777
+    _, gc = make_cfgs(so, solo, 2, 3, 128, True)
+    p0 = dev(synth.make_params(n))
+    g_host, g = grads_for("normal", n, 1e-3, 4242, True)
+    st = solo.SoloState(n, gc)
+    for step in (1, 2):                                   # a non-trivial state to start from
+        st.step(p0, g, step)
+    torch.cuda.synchronize()
+    init = [t.clone() for t in (p0, *st.buffers())]
+
+    def restore():
+        for dst, src in zip((p0, *st.buffers()), init):
+            dst.copy_(src)
+
+    st.step(p0, g, 3)                                     # eager result of step 3
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (p0, *st.buffers())]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    restore()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        st.step(p0, g, 3)                                 # launches on the capturing (current) stream
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        restore()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((p0, *st.buffers()), want):
+            assert torch.equal(got, ref)
+
+
 # ------------------------------------------------------- many tensors in one launch
 
 @pytest.mark.parametrize("bm,bv,B,bf16,de,optimizer,extras", [(2, 3, 128, True, False, "adamw", False),
