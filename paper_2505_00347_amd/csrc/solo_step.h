@@ -524,18 +524,34 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     float4 *const st_c = stage + (lane + lane / 8u);        // coalesced slots: st_c[0] and st_c[72] (= slot 64 + lane)
     float4 *const st_l = stage + (2u * lane + lane / 4u);   // this lane's 8 elements: st_l[0], st_l[1]
 
-    // ---- stage the super-tile's state in LDS (coalesced)
-    for (uint32_t w = lane; w < MW; w += 64) {
-        const uint64_t gw = tile * MW + w;
-        uint32_t x = (!TAIL || gw < m_total) ? a.m_words[gw] : 0u;
-        if (BM == 3) x &= 0x3FFFFFFFu;
-        img_m[w] = x;
-    }
-    for (uint32_t w = lane; w < VW; w += 64) {
-        const uint64_t gw = tile * VW + w;
-        uint32_t x = (!TAIL || gw < v_total) ? a.v_words[gw] : 0u;
-        if (BV == 3) x &= 0x3FFFFFFFu;
-        img_v[w] = x;
+    // ---- stage the super-tile's state in LDS (coalesced; full tiles move 16 bytes per lane)
+    static_assert(MW % 4 == 0 && VW % 4 == 0 && kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
+    if (!TAIL) {
+        const u32x4_t *gm = reinterpret_cast<const u32x4_t *>(a.m_words + tile * MW);
+        const u32x4_t *gv = reinterpret_cast<const u32x4_t *>(a.v_words + tile * VW);
+        for (uint32_t q = lane; q < MW / 4; q += 64) {
+            u32x4_t x = __builtin_nontemporal_load(gm + q);
+            if (BM == 3) x &= 0x3FFFFFFFu;
+            *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = x;
+        }
+        for (uint32_t q = lane; q < VW / 4; q += 64) {
+            u32x4_t x = __builtin_nontemporal_load(gv + q);
+            if (BV == 3) x &= 0x3FFFFFFFu;
+            *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = x;
+        }
+    } else {
+        for (uint32_t w = lane; w < MW; w += 64) {
+            const uint64_t gw = tile * MW + w;
+            uint32_t x = gw < m_total ? a.m_words[gw] : 0u;
+            if (BM == 3) x &= 0x3FFFFFFFu;
+            img_m[w] = x;
+        }
+        for (uint32_t w = lane; w < VW; w += 64) {
+            const uint64_t gw = tile * VW + w;
+            uint32_t x = gw < v_total ? a.v_words[gw] : 0u;
+            if (BV == 3) x &= 0x3FFFFFFFu;
+            img_v[w] = x;
+        }
     }
     if (lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
     for (uint32_t b = lane; b < NBT; b += 64) {
@@ -882,13 +898,22 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     // ---- write the super-tile's state back (coalesced)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    for (uint32_t w = lane; w < MW; w += 64) {
-        const uint64_t gw = tile * MW + w;
-        if (!TAIL || gw < m_total) a.m_words[gw] = img_m[w];
-    }
-    for (uint32_t w = lane; w < VW; w += 64) {
-        const uint64_t gw = tile * VW + w;
-        if (!TAIL || gw < v_total) a.v_words[gw] = img_v[w];
+    if (!TAIL) {
+        u32x4_t *gm = reinterpret_cast<u32x4_t *>(a.m_words + tile * MW);
+        u32x4_t *gv = reinterpret_cast<u32x4_t *>(a.v_words + tile * VW);
+        for (uint32_t q = lane; q < MW / 4; q += 64)
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(img_m + 4 * q), gm + q);
+        for (uint32_t q = lane; q < VW / 4; q += 64)
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(img_v + 4 * q), gv + q);
+    } else {
+        for (uint32_t w = lane; w < MW; w += 64) {
+            const uint64_t gw = tile * MW + w;
+            if (gw < m_total) a.m_words[gw] = img_m[w];
+        }
+        for (uint32_t w = lane; w < VW; w += 64) {
+            const uint64_t gw = tile * VW + w;
+            if (gw < v_total) a.v_words[gw] = img_v[w];
+        }
     }
     for (uint32_t b = lane; b < NBT; b += 64) {
         const uint64_t gb = tile * NBT + b;
