@@ -123,8 +123,10 @@ int solo_state_init(uint32_t *m_codes, float *m_scale,
  *   grad    float[n] or bf16[n] per cfg->grad_dtype, read only
  *   states  as laid out above, read and written
  *   step    1-based count of this update (bias correction and xi stream)
- * Gradients must be finite.  A block whose new maximum is below 2^-100 is
- * stored as a zero block. */
+ * Gradients must be finite and so must their squares in binary32 (|g| < 1.8e19);
+ * the result for other inputs is unspecified (no call hangs or faults: every loop
+ * of the kernels is bounded and every table index is clamped).  A block whose new
+ * maximum is below 2^-100 is stored as a zero block. */
 int solo_adamw_step(float *param, const void *grad,
                     uint32_t *m_codes, float *m_scale,
                     uint32_t *v_codes, float *v_scale, float *v_base,

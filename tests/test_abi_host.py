@@ -107,6 +107,47 @@ def test_error_strings_and_host_side_rejections(solo):
     assert solo.solo_state_init(16, 16, 16, 16, 16, 100, bad, stream=0, check=False) == solo.SOLO_E_INVALID
 
 
+def test_multi_tensor_table_layout(solo):
+    """The table of solo_adamw_step_multi is built by host code alone: 96 bytes per tensor
+    (eight pointers, n, first unit, xi offset, a reserved word), then one 32-bit tensor index per
+    unit.  The pointers are made-up, suitably aligned addresses; nothing touches a GPU."""
+    import numpy as np
+    cfg = solo.make_config(2, 3, 128, 1, index_offset=8 * 77)
+    sizes = [3000, 0, 5120, 12800 + 1, 64]
+    arr = (solo.solo_tensor * len(sizes))()
+    for k, n in enumerate(sizes):
+        base = 0x10000000 * (k + 1)
+        arr[k] = solo.solo_tensor(base, base + 0x1000000 if k == 2 else None, base + 0x2000000, base + 0x3000000,
+                                  base + 0x4000000, base + 0x5000000, base + 0x6000000, base + 0x7000000, n)
+    units = solo.solo_multi_units(arr, len(sizes), cfg)
+    unit = 5120 if units == 1 + 0 + 1 + 3 + 1 else 2560
+    per_tensor = [-(-n // unit) for n in sizes]
+    assert units == sum(per_tensor)
+    nbytes = solo.solo_multi_table_bytes(len(sizes), units)
+    assert nbytes == 96 * len(sizes) + 4 * units
+    buf = np.zeros(nbytes, np.uint8)
+    rc, flags = solo.solo_multi_table_build(arr, len(sizes), cfg, buf.ctypes.data, nbytes)
+    assert rc == solo.SOLO_OK and flags == 1                      # tensor 2 has a bf16 copy
+    entries = buf[:96 * len(sizes)].view(np.uint64).reshape(len(sizes), 12)
+    unit_map = buf[96 * len(sizes):].view(np.uint32)
+    unit0, xi = 0, 8 * 77
+    for k, n in enumerate(sizes):
+        base = 0x10000000 * (k + 1)
+        want_ptrs = [base, base + 0x1000000 if k == 2 else 0] + [base + 0x1000000 * j for j in range(2, 8)]
+        assert list(entries[k, :8]) == want_ptrs
+        assert entries[k, 8] == n and entries[k, 9] == unit0 and entries[k, 10] == xi
+        assert np.all(unit_map[unit0:unit0 + per_tensor[k]] == k)
+        unit0 += per_tensor[k]
+        xi += -(-n // 2560) * 2560                               # xi offsets advance in 2560-element steps
+    # a misaligned or missing pointer of a non-empty tensor is refused; an empty tensor's are ignored
+    arr[0].grad = arr[0].grad + 8
+    assert solo.solo_multi_table_build(arr, len(sizes), cfg, buf.ctypes.data, nbytes, check=False)[0] == solo.SOLO_E_INVALID
+    arr[0].grad = arr[0].grad - 8
+    arr[1].param = None
+    assert solo.solo_multi_table_build(arr, len(sizes), cfg, buf.ctypes.data, nbytes, check=False)[0] == solo.SOLO_OK
+    assert solo.solo_multi_units(arr, len(sizes), solo.make_config(2, 3, 100, 1)) == 0
+
+
 def test_product_does_not_import_the_oracle():
     """The library and its binding must not reach into oracle/ (tests, smoke and the
     benchmark's cpu_baseline leg are the only users)."""
