@@ -361,10 +361,21 @@ __device__ __forceinline__ uint4 stream_load_u4(const void *p)
     const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+// Streaming stores are non-temporal and written through at device scope (sc1): the data leaves
+// the L2 at once instead of waiting for an eviction, which drains the write stream more evenly
+// (0.5-1 % on the whole step over a plain non-temporal store).
+// (Written as assembly because no builtin sets sc1.  The s_nop covers the two wait states that a
+// store of more than 64 bits needs before its data registers may be overwritten: the compiler
+// keeps that distance for its own stores but does not look inside an asm block.)
+__device__ __forceinline__ void stream_store_u4(void *p, u32x4_t v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
 __device__ __forceinline__ void stream_store_f4(float *p, float4 x)
 {
-    const f32x4_t v = {x.x, x.y, x.z, x.w};
-    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p));
+    const u32x4_t v = {__builtin_bit_cast(uint32_t, x.x), __builtin_bit_cast(uint32_t, x.y),
+                       __builtin_bit_cast(uint32_t, x.z), __builtin_bit_cast(uint32_t, x.w)};
+    stream_store_u4(p, v);
 }
 
 // Two binary32 values rounded to bfloat16 (nearest, ties to even: the hardware conversion),
@@ -700,7 +711,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             if (!TAIL) {
                 const u32x4_t h = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
                                  pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-                __builtin_nontemporal_store(h, reinterpret_cast<u32x4_t *>(a.param_bf16 + e0));
+                stream_store_u4(a.param_bf16 + e0, h);
             } else {
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
@@ -902,9 +913,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         u32x4_t *gm = reinterpret_cast<u32x4_t *>(a.m_words + tile * MW);
         u32x4_t *gv = reinterpret_cast<u32x4_t *>(a.v_words + tile * VW);
         for (uint32_t q = lane; q < MW / 4; q += 64)
-            __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(img_m + 4 * q), gm + q);
+            stream_store_u4(gm + q, *reinterpret_cast<const u32x4_t *>(img_m + 4 * q));
         for (uint32_t q = lane; q < VW / 4; q += 64)
-            __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(img_v + 4 * q), gv + q);
+            stream_store_u4(gv + q, *reinterpret_cast<const u32x4_t *>(img_v + 4 * q));
     } else {
         for (uint32_t w = lane; w < MW; w += 64) {
             const uint64_t gw = tile * MW + w;
