@@ -58,8 +58,10 @@ __global__ __launch_bounds__(256) void k_step_shaped(float *__restrict__ p, cons
         const u32x4 gg = __builtin_nontemporal_load((const u32x4 *)(g + e + lane * 8));
         p0.x += __uint_as_float(gg.x << 16); p0.y += __uint_as_float(gg.y << 16);
         p1.x += __uint_as_float(gg.z << 16); p1.y += __uint_as_float(gg.w << 16);
-        __builtin_nontemporal_store(p0, (f32x4 *)(p + e + lane * 4));
-        __builtin_nontemporal_store(p1, (f32x4 *)(p + e + 256 + lane * 4));
+        // the step kernel's own store: non-temporal, written through at device scope; two wait
+        // states before the data registers of a 128-bit store may be reused
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p + e + lane * 4), "v"(p0) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p + e + 256 + lane * 4), "v"(p1) : "memory");
     }
 }
 
