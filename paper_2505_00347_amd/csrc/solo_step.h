@@ -538,17 +538,50 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     // ---- stage the super-tile's state in LDS (coalesced; full tiles move 16 bytes per lane)
     static_assert(MW % 4 == 0 && VW % 4 == 0 && kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
     if (!TAIL) {
+        // every load is issued before the first one is waited for: one memory round trip, not five
+        constexpr int RM = (MW / 4 + 63) / 64, RV = (VW / 4 + 63) / 64, RS = (NBT + 63) / 64;
         const u32x4_t *gm = reinterpret_cast<const u32x4_t *>(a.m_words + tile * MW);
         const u32x4_t *gv = reinterpret_cast<const u32x4_t *>(a.v_words + tile * VW);
-        for (uint32_t q = lane; q < MW / 4; q += 64) {
-            u32x4_t x = __builtin_nontemporal_load(gm + q);
-            if (BM == 3) x &= 0x3FFFFFFFu;
-            *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = x;
+        u32x4_t xm[RM], xv[RV];
+        float s_dm[RS], s_dv[RS], s_al[RS];
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < MW / 4) xm[r] = __builtin_nontemporal_load(gm + q);
         }
-        for (uint32_t q = lane; q < VW / 4; q += 64) {
-            u32x4_t x = __builtin_nontemporal_load(gv + q);
-            if (BV == 3) x &= 0x3FFFFFFFu;
-            *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = x;
+#pragma unroll
+        for (int r = 0; r < RV; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < VW / 4) xv[r] = __builtin_nontemporal_load(gv + q);
+        }
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            const uint32_t bb = lane + 64u * r;
+            if (bb < NBT) {
+                const uint64_t gb = tile * NBT + bb;
+                s_dm[r] = a.m_scale[gb]; s_dv[r] = a.v_scale[gb]; s_al[r] = a.v_base[gb];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < MW / 4) {
+                if (BM == 3) xm[r] &= 0x3FFFFFFFu;
+                *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = xm[r];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RV; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < VW / 4) {
+                if (BV == 3) xv[r] &= 0x3FFFFFFFu;
+                *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = xv[r];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            const uint32_t bb = lane + 64u * r;
+            if (bb < NBT) { sc[bb] = s_dm[r]; sc[NBT + bb] = s_dv[r]; sc[2 * NBT + bb] = s_al[r]; }
         }
     } else {
         for (uint32_t w = lane; w < MW; w += 64) {
@@ -563,15 +596,15 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             if (BV == 3) x &= 0x3FFFFFFFu;
             img_v[w] = x;
         }
+        for (uint32_t b = lane; b < NBT; b += 64) {
+            const uint64_t gb = tile * NBT + b;
+            const bool ok = gb < nblk;
+            sc[b] = ok ? a.m_scale[gb] : 0.0f;
+            sc[NBT + b] = ok ? a.v_scale[gb] : 0.0f;
+            sc[2 * NBT + b] = ok ? a.v_base[gb] : 1.0f;
+        }
     }
     if (lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
-    for (uint32_t b = lane; b < NBT; b += 64) {
-        const uint64_t gb = tile * NBT + b;
-        const bool ok = !TAIL || gb < nblk;
-        sc[b] = ok ? a.m_scale[gb] : 0.0f;
-        sc[NBT + b] = ok ? a.v_scale[gb] : 0.0f;
-        sc[2 * NBT + b] = ok ? a.v_base[gb] : 1.0f;
-    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
