@@ -58,6 +58,7 @@ constexpr int kLdsPerCu = 160 * 1024;
 #define SOLO_WAVES 4
 #endif
 constexpr int kWaves = SOLO_WAVES; // wavefronts per workgroup
+static_assert(kWaves >= 2, "the ragged end of a flat buffer is launched as up to two wavefronts of one workgroup");
 constexpr int kXcds = 8;           // accelerator dies of an MI355X (each has its own L2)
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
