@@ -895,10 +895,15 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
                     const u32x2_t e = *(lds_u32x2_t *)(uintptr_t)addr;
                     code = e.y + (z > u2f(e.x) ? 1u : 0u);
                 } else {
-                    uint32_t cnt = 0;
+                    // few levels: the code is the number of rounding boundaries below z.  A value
+                    // on a boundary keeps the level of smaller magnitude: '>' on the positive side,
+                    // '>=' on the negative one (z = -0 is above every negative boundary: code L).
+                    (void)az;
+                    code = 0;
 #pragma unroll
-                    for (int k = 0; k <= L; ++k) cnt += (az > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
-                    code = (z < 0.0f) ? (uint32_t)L - umin(cnt, (uint32_t)L) : (uint32_t)L + cnt;
+                    for (int k = 0; k < L; ++k) code += (z >= -DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
+#pragma unroll
+                    for (int k = 0; k <= L; ++k) code += (z > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
                 }
                 if (TAIL && !ok[j]) code = 0;
                 m8_de |= code << (BM * j);
