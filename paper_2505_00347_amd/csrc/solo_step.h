@@ -13,7 +13,11 @@
 //
 // step_tile() is the whole step for one super-tile; step_kernel runs it over
 // a flat buffer (full tiles, and the ragged end with bounds checks),
-// multi_kernel over the tensors of a caller-built table.
+// multi_kernel over the tensors of a caller-built table.  Full super-tiles of
+// formats with 128-element blocks whose state image is small enough take
+// step_tile16() instead: 16 elements per lane, 8 lanes per block, 1024
+// elements per iteration, four wavefronts per SIMD instead of five (fewer
+// instructions per element; see there).
 //
 // The kernel is bound by vector-ALU issue as much as by HBM (packed FP32 is
 // off, so a CU retires 64 lane-operations per clock: about 80 per parameter at
@@ -61,6 +65,9 @@ constexpr int kWaves = SOLO_WAVES; // wavefronts per workgroup
 static_assert(kWaves >= 2, "the ragged end of a flat buffer is launched as up to two wavefronts of one workgroup");
 constexpr int kXcds = 8;           // accelerator dies of an MI355X (each has its own L2)
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
+constexpr int kIter16 = 1024;      // elements per iteration of the wide path (64 lanes x 16)
+constexpr int kColStride16 = 20;   // its column stride (16 keys, +inf, pad)
+constexpr int kWideWaves = 4;      // wavefronts per SIMD the wide path is compiled for
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
 constexpr float kRhoMin = 0x1p-64f;
 constexpr uint32_t kInfBits = 0x7F800000u;
@@ -232,6 +239,40 @@ __device__ __noinline__ uint32_t walk_base(uint32_t y, float rho)
     for (int i = 0; i < 4096 && last_level<BV>(u2f(y)) > rho; ++i) --y;
     for (int i = 0; i < 4096 && y < kOneBits && last_level<BV>(u2f(y + 1)) <= rho; ++i) ++y;
     return y;
+}
+
+// The base alpha = rho^(1/K) as stored: the largest binary32 whose last level does not exceed rho.
+// The hardware exp2/log2 give a guess that is a few units in the last place off; the lanes of the
+// group test the 16 consecutive binary32 values yb - 8 .. yb + 7 around it in parallel (one per
+// lane in a group of 16, two per lane in a group of 8) and count those that fit.  Only a guess
+// further off than that takes the bounded walk.  Returns the bit pattern; meaningful if rho < 1.
+template <int BV, int G>
+__device__ __forceinline__ uint32_t search_base(float rho, bool need, uint32_t lane, uint32_t lig, uint32_t gshift)
+{
+    constexpr int K = (1 << BV) - 1;
+    constexpr float invK = 1.0f / (float)K;
+    constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
+    static_assert(G == 8 || G == 16, "group of 8 or 16 lanes");
+    const float y0 = __builtin_amdgcn_exp2f(__builtin_amdgcn_logf(rho) * invK);
+    const uint32_t yb = umed3(f2u(y0), 0x00800000u, kOneBits);
+    uint32_t cnt;
+    if (G == 16) {
+        const uint32_t cand = umin(yb + lig - 8u, kOneBits);
+        const bool fits = last_level<BV>(u2f(cand)) <= rho;
+        cnt = (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits), lane, gshift, GMASK));
+    } else {
+        const uint32_t cand0 = umin(yb + lig - 8u, kOneBits), cand1 = umin(yb + lig, kOneBits);
+        const bool fits0 = last_level<BV>(u2f(cand0)) <= rho, fits1 = last_level<BV>(u2f(cand1)) <= rho;
+        cnt = (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits0), lane, gshift, GMASK)) +
+              (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits1), lane, gshift, GMASK));
+    }
+    uint32_t ab = umin(yb + cnt - 9u, kOneBits);
+    // not bracketed (all or none of the candidates fit): walk from the nearest end
+    const bool open = need && (cnt == 0u || cnt == 16u);
+    if (__builtin_amdgcn_ballot_w64(open) != 0) {
+        if (open) ab = walk_base<BV>(cnt == 0u ? yb - 8u : ab, rho);
+    }
+    return ab;
 }
 
 // Eight consecutive BITS-wide codes starting at slot `slot` of word w0 (the
@@ -444,20 +485,24 @@ __device__ __forceinline__ void wave_lds_sync()
 //   img_m/v   the super-tile's code words (loaded once, updated in place, written back once)
 //   tv, tm    level tables of the blocks of the current iteration
 //   sc        3 block scalars (Delta_m, Delta_v, alpha) per block of the super-tile
-template <int BM, int BV, int B, bool MDE, int TILE>
+template <int BM, int BV, int B, bool MDE, int TILE, int E = 8>
 struct SlabLayout {
-    static constexpr int NG = 64 / (B / 8);
+    static constexpr int NG = 64 / (B / E);
+    static constexpr int kCol = E == 8 ? kColStride : kColStride16;
     static constexpr int NBT = TILE / B;
     static constexpr int MW = TILE / (32 / BM), VW = TILE / (32 / BV);
     static constexpr int VT = 1 << BV;
-    static constexpr int MTS = 16;
+    static constexpr int MTS = BM == 2 ? 4 : BM == 3 ? 8 : 16;   // stride of the m tables: a power of two >= their entries
     static constexpr int kOffCol = 0;
-    static constexpr int kOffImgM = 64 * kColStride;
+    static constexpr int kOffImgM = 64 * kCol;
     static constexpr int kOffImgV = kOffImgM + ((MW + 4 + 3) / 4) * 4;
     static constexpr int kOffTv = ((kOffImgV + VW + 4 + 15) / 16) * 16;      // 64-byte aligned
     static constexpr int kOffTm = kOffTv + ((NG * VT + 15) / 16) * 16;
     static constexpr int kOffSc = kOffTm + NG * MTS;
-    static constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16;
+#ifndef SOLO_PAD_SLAB
+#define SOLO_PAD_SLAB 0
+#endif
+    static constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16 + SOLO_PAD_SLAB;
     static constexpr bool kDeTable = MDE && BM >= 3;     // DE rounding by bucket table (two boundaries: compares are cheaper)
     static constexpr int kDeWords = kDeTable ? 4 * DeBuckets<BM>::N : 16;
     static constexpr int kBytesPerWg = 4 * (kWaves * kSlab + kDeWords);
@@ -466,10 +511,23 @@ struct SlabLayout {
 // Elements per wavefront super-tile: a longer tile spreads a wavefront's start-up (kernel
 // arguments, first loads) over more work, so the tile is doubled wherever the larger state
 // image still leaves room for SOLO_MIN_WAVES wavefronts per SIMD.
+// The wide path (16 elements per lane, see step_tile16) serves the full super-tiles of a format
+// with 128-element blocks whenever its larger LDS slab lets kWideWaves wavefronts per SIMD run.
+#ifndef SOLO_WIDE
+#define SOLO_WIDE 1
+#endif
+template <int BM, int BV, int B, bool MDE>
+constexpr bool wide_path()
+{
+    constexpr int wgs = kWideWaves * 4 / kWaves;
+    return SOLO_WIDE && B == 128 && SlabLayout<BM, BV, 128, MDE, 2 * kTileUnit, 16>::kBytesPerWg * wgs <= kLdsPerCu;
+}
+
 template <int BM, int BV, int B, bool MDE>
 constexpr int tile_elems()
 {
     constexpr int wgs = SOLO_MIN_WAVES * 4 / kWaves;              // workgroups per CU at that occupancy
+    if (wide_path<BM, BV, B, MDE>()) return 2 * kTileUnit;
     return SlabLayout<BM, BV, B, MDE, 2 * kTileUnit>::kBytesPerWg * wgs <= kLdsPerCu ? 2 * kTileUnit : kTileUnit;
 }
 
@@ -516,7 +574,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
     constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
     constexpr bool kDeTable = Lay::kDeTable;
-    static_assert(kSlab >= 64 * kColStride + 136, "column slack");
+    static_assert(kSlab >= 64 * kColStride + 140, "column slack");
 
     const uint64_t nblk = (a.n + B - 1) / B;
     const uint64_t m_total = (a.n + CM - 1) / CM, v_total = (a.n + CV - 1) / CV;
@@ -803,6 +861,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         if (!TAIL) {
             // Full tiles: the pop is written out (run the holders under their own exec mask), so
             // that a round is straight-line code with the loop's back edge as its only branch.
+            // A lane keeps the key behind its head in a register: a pop moves it up and fetches
+            // the one after it, whose LDS latency then lies outside the chain of rounds (it is
+            // waited for only when the same lane pops again).
+            uint32_t behind = key[1];
             for (uint32_t k = 0; k < a.rank_full; ++k) {
                 const uint32_t mn = group_reduce<G>(head, UMin());
                 uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
@@ -819,14 +881,17 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
                 uint64_t saved;
                 asm volatile("s_mov_b64 %[saved], exec\n\t"
                              "s_mov_b64 exec, %[holders]\n\t"
-                             "ds_read_b32 %[head], %[haddr] offset:4\n\t"
+                             "s_waitcnt lgkmcnt(0)\n\t"
+                             "v_mov_b32_e32 %[head], %[behind]\n\t"
+                             "ds_read_b32 %[behind], %[haddr] offset:8\n\t"
                              "v_add_u32_e32 %[haddr], 4, %[haddr]\n\t"
-                             "s_mov_b64 exec, %[saved]\n\t"
-                             "s_waitcnt lgkmcnt(0)"
-                             : [head] "+v"(head), [haddr] "+v"(haddr), [saved] "=&s"(saved)
+                             "s_mov_b64 exec, %[saved]"
+                             : [head] "+v"(head), [behind] "+v"(behind), [haddr] "+v"(haddr), [saved] "=&s"(saved)
                              : [holders] "s"(holders)
                              : "memory");
             }
+            // the last fetch may still be in flight: its register is free only once it has landed
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(behind) : : "memory");
         } else {
             for (uint32_t k = 0; k < a.rank_full; ++k) extract_round(k);
         }
@@ -841,23 +906,11 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         rho = dv > 0.0f ? rho : 1.0f;
         rho = rho < kRhoMin ? kRhoMin : rho;
 
-        // ---- alpha: largest binary32 whose last level is <= rho; one candidate per lane
+        // ---- alpha: largest binary32 whose last level is <= rho
         float alpha = 1.0f, inv_l2a = 0.0f, rdv = 0.0f, bias = 1.0f;
         {
-            constexpr float invK = 1.0f / (float)K;
             const bool need = rho < 1.0f;
-            const float y0 = __builtin_amdgcn_exp2f(__builtin_amdgcn_logf(rho) * invK);
-            const uint32_t yb = umed3(f2u(y0), 0x00800000u, kOneBits);
-            const uint32_t cand = umin(yb + lig - (uint32_t)(G / 2), kOneBits);
-            const bool fits = last_level<BV>(u2f(cand)) <= rho;
-            const uint32_t cnt = (uint32_t)__builtin_popcount(
-                group_bits(__builtin_amdgcn_ballot_w64(fits), lane, gshift, GMASK));
-            uint32_t ab = umin(yb + cnt - 1u - (uint32_t)(G / 2), kOneBits);
-            // not bracketed (all or none of the candidates fit): walk from the nearest end
-            const bool open = need && (cnt == 0u || cnt == (uint32_t)G);
-            if (__builtin_amdgcn_ballot_w64(open) != 0) {
-                if (open) ab = walk_base<BV>(cnt == 0u ? yb - (uint32_t)(G / 2) : ab, rho);
-            }
+            const uint32_t ab = search_base<BV, G>(rho, need, lane, lig, gshift);
             if (need) {
                 alpha = u2f(ab);
                 inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(alpha));
@@ -913,8 +966,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, f));
             tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));   // +inf (v^ = 0) takes the last code
             if (TAIL && !ok[j]) { tm = -(float)L; tv = 1.0f; }
-            if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
-            else        { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
+            if (j == 7)      { am_hi = tm; av_hi = tv; }
+            else if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
+            else if (j == 3) { am_lo = tm; av_lo = tv; }
+            else             { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
         }
         constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));   // L * sum 2^(BM j), j < 4
         constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
@@ -975,6 +1030,458 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     }
 }
 
+// Sixteen keys: two eight-sorts and Batcher's odd-even merge of the halves (25 exchanges).
+__device__ __forceinline__ void sort16(uint32_t (&k)[16])
+{
+    uint32_t lo[8], hi[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { lo[i] = k[i]; hi[i] = k[i + 8]; }
+    sort8(lo); sort8(hi);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { k[i] = lo[i]; k[i + 8] = hi[i]; }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cswap(k[i], k[i + 8]);
+#pragma unroll
+    for (int i = 4; i < 8; ++i) cswap(k[i], k[i + 4]);
+#pragma unroll
+    for (int i = 2; i < 12; i += 4) { cswap(k[i], k[i + 2]); cswap(k[i + 1], k[i + 3]); }
+#pragma unroll
+    for (int i = 1; i < 15; i += 2) cswap(k[i], k[i + 1]);
+}
+
+// Parameters and gradients of one lane and one 1024-element iteration of the wide path, in the
+// coalesced layout they are loaded in (vector k of a lane is vector lane + 64 k of the chunk).
+template <bool BF16>
+struct RawPG16 { float4 p[4]; uint4 g[BF16 ? 2 : 4]; };
+
+template <bool BF16>
+__device__ __forceinline__ RawPG16<BF16> load_pg16(const StepArgs &a, uint64_t chunk_e0, uint32_t lane)
+{
+    RawPG16<BF16> r;
+    const float *pp = a.param + chunk_e0 + lane * 4u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r.p[k] = stream_load_f4(pp + 256 * k);
+    if (BF16) {
+        const uint16_t *gp = static_cast<const uint16_t *>(a.grad) + chunk_e0 + lane * 8u;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) r.g[k] = stream_load_u4(gp + 512 * k);
+    } else {
+        const float *gp = static_cast<const float *>(a.grad) + chunk_e0 + lane * 4u;
+#pragma unroll
+        for (int k = 0; k < (BF16 ? 2 : 4); ++k) r.g[k] = stream_load_u4(gp + 256 * k);
+    }
+    return r;
+}
+
+// The wide path: the same step as step_tile() for a full super-tile of 128-element blocks, with
+// 16 consecutive elements per lane and 1024 per iteration.  A block is held by 8 lanes, so the
+// work that is done once per lane and block (level tables, the division, the base, the hash,
+// packing) is spread over twice as many elements, a group reduction is three DPP steps instead
+// of four, and a block still needs only r extraction rounds.  The price is registers (four
+// wavefronts per SIMD instead of five) and a 16-key sort per lane.
+template <int BM, int BV, bool BF16, bool MDE, bool EXT, int TILE>
+__device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t tile, const uint32_t lane,
+                                            uint32_t *const slab, const uint32_t *const lds_de)
+{
+    constexpr int B = 128, E = 16;
+    constexpr int G = B / E;                       // lanes per block (8)
+    constexpr int NG = 64 / G;                     // blocks per iteration (8)
+    constexpr int kTile = TILE;
+    constexpr int kIters = kTile / kIter16;
+    static_assert(kTile % kIter16 == 0, "whole iterations");
+    using Lay = SlabLayout<BM, BV, B, MDE, kTile, E>;
+    constexpr int NBT = kTile / B;
+    constexpr int L = (1 << (BM - 1)) - 1;
+    constexpr int K = (1 << BV) - 1;
+    constexpr int CM = 32 / BM, CV = 32 / BV;
+    constexpr int MW = kTile / CM, VW = kTile / CV;
+    constexpr int VT = K + 1;
+    constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
+    constexpr int MTS = Lay::MTS;
+    constexpr uint32_t GMASK = 0xFFu;
+    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
+    constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
+    constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
+    constexpr bool kDeTable = Lay::kDeTable;
+    // A runaway column address (possible only with non-finite input) stays inside the slab.
+    static_assert(kSlab >= 64 * kColStride16 + 140, "column slack");
+
+    const uint64_t tile_e0 = tile * kTile;
+    uint32_t *const img_m = slab + kOffImgM, *const img_v = slab + kOffImgV;
+    float *const sc = reinterpret_cast<float *>(slab + kOffSc);
+    uint32_t *const col = slab + kOffCol + lane * kColStride16;
+
+    RawPG16<BF16> raw = load_pg16<BF16>(a, tile_e0, lane);
+    const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;
+    // Layout transposition through LDS, 16-byte vectors.  Four vectors per lane (fp32): vector i
+    // of the chunk sits in slot i + i / 4, so that both the coalesced side (i = lane + 64 k) and
+    // the lane's own side (i = 4 lane + c, slot 5 lane + c) spread over the banks.  Two vectors
+    // per lane (bf16): slot i + i / 8.
+    static_assert(320 * 4 <= 64 * kColStride16, "staging must fit the column area");
+    float4 *const stage = reinterpret_cast<float4 *>(slab + kOffCol);
+    float4 *const st4_c = stage + (lane + lane / 4u);       // + 80 k
+    float4 *const st4_l = stage + 5u * lane;                // + c
+    float4 *const st2_c = stage + (lane + lane / 8u);       // + 72 k
+    float4 *const st2_l = stage + (2u * lane + lane / 4u);  // + c
+
+    // ---- stage the super-tile's state in LDS: every load is issued before the first wait
+    static_assert(MW % 4 == 0 && VW % 4 == 0 && kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
+    {
+        constexpr int RM = (MW / 4 + 63) / 64, RV = (VW / 4 + 63) / 64, RS = (NBT + 63) / 64;
+        const u32x4_t *gm = reinterpret_cast<const u32x4_t *>(a.m_words + tile * MW);
+        const u32x4_t *gv = reinterpret_cast<const u32x4_t *>(a.v_words + tile * VW);
+        u32x4_t xm[RM], xv[RV];
+        float s_dm[RS], s_dv[RS], s_al[RS];
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < MW / 4) xm[r] = __builtin_nontemporal_load(gm + q);
+        }
+#pragma unroll
+        for (int r = 0; r < RV; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < VW / 4) xv[r] = __builtin_nontemporal_load(gv + q);
+        }
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            const uint32_t bb = lane + 64u * r;
+            if (bb < NBT) {
+                const uint64_t gb = tile * NBT + bb;
+                s_dm[r] = a.m_scale[gb]; s_dv[r] = a.v_scale[gb]; s_al[r] = a.v_base[gb];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < MW / 4) {
+                if (BM == 3) xm[r] &= 0x3FFFFFFFu;
+                *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = xm[r];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RV; ++r) {
+            const uint32_t q = lane + 64u * r;
+            if (q < VW / 4) {
+                if (BV == 3) xv[r] &= 0x3FFFFFFFu;
+                *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = xv[r];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            const uint32_t bb = lane + 64u * r;
+            if (bb < NBT) { sc[bb] = s_dm[r]; sc[NBT + bb] = s_dv[r]; sc[2 * NBT + bb] = s_al[r]; }
+        }
+    }
+    if (lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    const uint32_t lig = lane & (G - 1);
+    const uint32_t grp = lane / G;
+    const uint32_t gshift = lane & 31u & ~(uint32_t)(G - 1);
+    float *const my_tv = reinterpret_cast<float *>(slab + kOffTv) + grp * VT;
+    float *const my_tm = reinterpret_cast<float *>(slab + kOffTm) + grp * MTS;
+    const uint32_t tv_addr = lds_addr(my_tv), tm_addr = lds_addr(my_tm);
+    const uint32_t col_addr = lds_addr(col);
+    // word and slot of the first code of the lane's two runs of 8 in iteration 0; an iteration
+    // advances every stream by 1024 codes
+    uint32_t wm[2], sm[2], wv[2], sv[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        wm[r] = (lane * 16u + 8u * r) / CM; sm[r] = (lane * 16u + 8u * r) % CM;
+        wv[r] = (lane * 16u + 8u * r) / CV; sv[r] = (lane * 16u + 8u * r) % CV;
+    }
+
+    float de_level[(16 + G - 1) / G];
+    uint32_t de_base = 0;
+    if (MDE) {
+#pragma unroll
+        for (int r = 0; r < (MT + G - 1) / G; ++r) de_level[r] = DeLevels<BM>::level(lig + r * G);
+        if (kDeTable) de_base = lds_addr(lds_de) - 16u * DeBuckets<BM>::kLo;
+    }
+
+#pragma unroll 1
+    for (int it = 0; it < kIters; ++it) {
+        const uint32_t e_loc = (uint32_t)it * kIter16 + lane * 16u;
+        const uint64_t e0 = tile_e0 + e_loc;
+        const uint32_t bl = (uint32_t)it * NG + grp;
+
+        // ---- old state of the block and of this lane's elements (LDS)
+        const float dm_old = sc[bl], dv_old = sc[NBT + bl], al_old = sc[2 * NBT + bl];
+        uint32_t mc8[2], vc8[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const uint32_t mw0 = img_m[wm[r]], mw1 = (BM == 3) ? img_m[wm[r] + 1] : 0u;
+            const uint32_t vw0 = img_v[wv[r]], vw1 = (BV == 3) ? img_v[wv[r] + 1] : 0u;
+            mc8[r] = extract8<BM>(mw0, mw1, sm[r]) & (uint32_t)((1ull << (8 * BM)) - 1ull);
+            vc8[r] = extract8<BV>(vw0, vw1, sv[r]) & (uint32_t)((1ull << (8 * BV)) - 1ull);
+        }
+
+        // ---- level tables of this lane's block: entries lig, lig + G
+        {
+            const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
+            const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
+#pragma unroll
+            for (int r = 0; r < (VT + G - 1) / G; ++r) {
+                const uint32_t q = lig + r * G;
+                if (q < VT) my_tv[q] = log_level<BV>(q, P1, P2, P4, P8) * dv_old;
+            }
+#pragma unroll
+            for (int r = 0; r < (MT + G - 1) / G; ++r) {
+                const uint32_t c = lig + r * G;
+                if (c < MT) my_tm[c] = MDE ? de_level[r] * dm_old : (float)((int)c - L) * s_m;
+            }
+        }
+
+        // ---- coalesced layout -> 16 consecutive elements per lane
+        float p[16], g[16];
+        {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) st4_c[80 * k] = raw.p[k];
+            wave_lds_sync();                   // (also orders the level tables before their readers)
+            float4 t[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) t[c] = st4_l[c];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { p[4 * c] = t[c].x; p[4 * c + 1] = t[c].y; p[4 * c + 2] = t[c].z; p[4 * c + 3] = t[c].w; }
+            wave_lds_sync();
+            if (BF16) {
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    st2_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+                wave_lds_sync();
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const float4 x = st2_l[c];
+                    const uint32_t w[4] = {f2u(x.x), f2u(x.y), f2u(x.z), f2u(x.w)};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        g[8 * c + 2 * i] = u2f(w[i] << 16);
+                        g[8 * c + 2 * i + 1] = u2f(w[i] & 0xFFFF0000u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < (BF16 ? 2 : 4); ++k)
+                    st4_c[80 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+                wave_lds_sync();
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float4 x = st4_l[c];
+                    g[4 * c] = x.x; g[4 * c + 1] = x.y; g[4 * c + 2] = x.z; g[4 * c + 3] = x.w;
+                }
+            }
+        }
+        if (EXT) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
+        }
+        // next iteration's parameters and gradients, a whole iteration ahead of their use
+        if (it + 1 < kIters) raw = load_pg16<BF16>(a, tile_e0 + (uint32_t)(it + 1) * kIter16, lane);
+
+        // ---- dequantize (table look-up), EMA, parameter
+        float mh[16], vh[16];
+        float m_absmax = 0.0f, v_max = 0.0f;
+        const float kb = a.belief ? 1.0f : 0.0f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int r = j / 8, jj = j % 8;
+            const uint32_t om = (jj == 0) ? (mc8[r] << 2) : (mc8[r] >> (BM * jj - 2));
+            const uint32_t ov = (jj == 0) ? (vc8[r] << 2) : (vc8[r] >> (BV * jj - 2));
+            const float mt = lds_f32(tm_addr | (om & MIDX));
+            const float vt = lds_f32(tv_addr | (ov & VIDX));
+            mh[j] = __builtin_fmaf(a.beta1, mt, a.omb1 * g[j]);
+            if (EXT) {
+                const float d = __builtin_fmaf(-kb, mh[j], g[j]);
+                vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (d * d)) + a.eps_state;
+            } else {
+                vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (g[j] * g[j]));
+            }
+            const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
+            p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
+            m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
+            v_max = __builtin_fmaxf(v_max, vh[j]);
+        }
+        // ---- new parameters back to the coalesced layout, streamed out
+        wave_lds_sync();
+        if (EXT && a.param_bf16) {               // 16-bit copy first: 32 bytes per lane, two vectors
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint32_t h0 = pack_bf16(p[8 * c], p[8 * c + 1]), h1 = pack_bf16(p[8 * c + 2], p[8 * c + 3]);
+                const uint32_t h2 = pack_bf16(p[8 * c + 4], p[8 * c + 5]), h3 = pack_bf16(p[8 * c + 6], p[8 * c + 7]);
+                st2_l[c] = make_float4(u2f(h0), u2f(h1), u2f(h2), u2f(h3));
+            }
+            wave_lds_sync();
+            uint16_t *hp = a.param_bf16 + (tile_e0 + (uint32_t)it * kIter16) + lane * 8u;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) stream_store_f4(reinterpret_cast<float *>(hp + 512 * k), st2_c[72 * k]);
+            wave_lds_sync();
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) st4_l[c] = make_float4(p[4 * c], p[4 * c + 1], p[4 * c + 2], p[4 * c + 3]);
+        wave_lds_sync();
+        {
+            float *pp = a.param + (tile_e0 + (uint32_t)it * kIter16) + lane * 4u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st4_c[80 * k]);
+        }
+        wave_lds_sync();                        // the staging area becomes the column area
+
+        // ---- block maxima
+        float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
+        float dv = u2f(group_reduce<G>(f2u(v_max), UMax()));
+        if (dm < kTiny) dm = 0.0f;
+        if (dv < kTiny) dv = 0.0f;
+
+        // ---- the r-th smallest v^ of the block
+        uint32_t xp_bits = 0;
+        {
+            uint32_t key[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) key[j] = f2u(vh[j]);
+            sort16(key);
+            col[16] = kInfBits;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                *reinterpret_cast<uint4 *>(col + 4 * c) = make_uint4(key[4 * c], key[4 * c + 1], key[4 * c + 2], key[4 * c + 3]);
+            uint32_t head = key[0], behind = key[1], haddr = col_addr;
+            for (uint32_t k = 0; k < a.rank_full; ++k) {
+                const uint32_t mn = group_reduce<G>(head, UMin());
+                uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
+                if (__builtin_expect(__builtin_popcountll(holders) != NG, 0)) {
+                    uint64_t lowest = 0;           // a tie: the lowest holder of each group pops
+#pragma unroll
+                    for (int gi = 0; gi < NG; ++gi) {
+                        const uint64_t f = (holders >> (gi * G)) & (uint64_t)GMASK;
+                        lowest |= (f & (0 - f)) << (gi * G);
+                    }
+                    holders = lowest;
+                }
+                xp_bits = mn;
+                uint64_t saved;
+                asm volatile("s_mov_b64 %[saved], exec\n\t"
+                             "s_mov_b64 exec, %[holders]\n\t"
+                             "s_waitcnt lgkmcnt(0)\n\t"
+                             "v_mov_b32_e32 %[head], %[behind]\n\t"
+                             "ds_read_b32 %[behind], %[haddr] offset:8\n\t"
+                             "v_add_u32_e32 %[haddr], 4, %[haddr]\n\t"
+                             "s_mov_b64 exec, %[saved]"
+                             : [head] "+v"(head), [behind] "+v"(behind), [haddr] "+v"(haddr), [saved] "=&s"(saved)
+                             : [holders] "s"(holders)
+                             : "memory");
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(behind) : : "memory");
+        }
+
+        // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
+        const float num = (lane & 1u) ? (MDE ? 1.0f : (float)L) : u2f(xp_bits);
+        const float den = (lane & 1u) ? dm : dv;
+        const float quo = num / den;
+        float rho = u2f(dpp<0xA0>(f2u(quo)));
+        float inv_s = u2f(dpp<0xF5>(f2u(quo)));
+        inv_s = dm > 0.0f ? inv_s : 0.0f;
+        rho = dv > 0.0f ? rho : 1.0f;
+        rho = rho < kRhoMin ? kRhoMin : rho;
+
+        // ---- alpha: largest binary32 whose last level is <= rho
+        float alpha = 1.0f, inv_l2a = 0.0f, rdv = 0.0f, bias = 1.0f;
+        {
+            const bool need = rho < 1.0f;
+            const uint32_t ab = search_base<BV, G>(rho, need, lane, lig, gshift);
+            if (need) {
+                alpha = u2f(ab);
+                inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(alpha));
+                rdv = __builtin_amdgcn_rcpf(dv);
+                bias = 0.0f;
+            }
+        }
+
+        // ---- encode and update the state image, one run of 8 elements at a time
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const uint64_t gidx = (a.index_offset + e0 + 8u * r) >> 3;
+            uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
+            uint32_t Y = mix32(X ^ a.key1) | 1u;
+            if (!a.stochastic) { X = 0x80000000u; Y = 0u; }
+            float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
+            uint32_t m8_de = 0;
+#pragma unroll
+            for (int j = 7; j >= 0; --j) {
+                const float mhj = mh[8 * r + j], vhj = vh[8 * r + j];
+                float tm = 0.0f;
+                if (!MDE) {
+                    tm = __builtin_rintf(mhj * inv_s);
+                } else {
+                    const float z = mhj * inv_s;
+                    uint32_t code;
+                    if (kDeTable) {
+                        const uint32_t bk = umin(umax(__builtin_amdgcn_ubfe(f2u(z), 21u, 10u), DeBuckets<BM>::kLo),
+                                                 DeBuckets<BM>::kHi);
+                        const uint32_t addr = ((f2u(z) >> 28) & 8u) | ((bk << 4) + de_base);
+                        const u32x2_t e = *(lds_u32x2_t *)(uintptr_t)addr;
+                        code = e.y + (z > u2f(e.x) ? 1u : 0u);
+                    } else {
+                        code = 0;
+#pragma unroll
+                        for (int k = 0; k < L; ++k) code += (z >= -DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
+#pragma unroll
+                        for (int k = 0; k <= L; ++k) code += (z > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
+                    }
+                    m8_de |= code << (BM * j);
+                }
+                const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, X + (uint32_t)j * Y, 9u));
+                const float ratio = __builtin_fmaf(vhj, rdv, bias);
+                float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, f));
+                tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));
+                if (j == 7)      { am_hi = tm; av_hi = tv; }
+                else if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
+                else if (j == 3) { am_lo = tm; av_lo = tv; }
+                else             { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
+            }
+            constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));
+            constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));
+            const uint32_t m8 = MDE ? m8_de : ((uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM)));
+            const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
+            const uint32_t xm = mc8[r] ^ m8, xv = vc8[r] ^ v8;
+            if (BM == 3) {
+                atomicXor(&img_m[wm[r]], (xm << (3u * sm[r])) & 0x3FFFFFFFu);
+                atomicXor(&img_m[wm[r] + 1], (uint32_t)(((uint64_t)xm << (3u * sm[r])) >> 30));
+            } else {
+                atomicXor(&img_m[wm[r]], xm << (BM * sm[r]));
+            }
+            if (BV == 3) {
+                atomicXor(&img_v[wv[r]], (xv << (3u * sv[r])) & 0x3FFFFFFFu);
+                atomicXor(&img_v[wv[r] + 1], (uint32_t)(((uint64_t)xv << (3u * sv[r])) >> 30));
+            } else {
+                atomicXor(&img_v[wv[r]], xv << (BV * sv[r]));
+            }
+            wm[r] += kIter16 / CM; sm[r] += kIter16 % CM;
+            if (sm[r] >= (uint32_t)CM) { sm[r] -= CM; wm[r] += 1; }
+            wv[r] += kIter16 / CV; sv[r] += kIter16 % CV;
+            if (sv[r] >= (uint32_t)CV) { sv[r] -= CV; wv[r] += 1; }
+        }
+        if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
+    }
+
+    // ---- write the super-tile's state back (coalesced)
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    {
+        u32x4_t *gm = reinterpret_cast<u32x4_t *>(a.m_words + tile * MW);
+        u32x4_t *gv = reinterpret_cast<u32x4_t *>(a.v_words + tile * VW);
+        for (uint32_t q = lane; q < MW / 4; q += 64)
+            stream_store_u4(gm + q, *reinterpret_cast<const u32x4_t *>(img_m + 4 * q));
+        for (uint32_t q = lane; q < VW / 4; q += 64)
+            stream_store_u4(gv + q, *reinterpret_cast<const u32x4_t *>(img_v + 4 * q));
+    }
+    for (uint32_t b = lane; b < NBT; b += 64) {
+        const uint64_t gb = tile * NBT + b;
+        a.m_scale[gb] = sc[b];
+        a.v_scale[gb] = sc[NBT + b];
+        a.v_base[gb] = sc[2 * NBT + b];
+    }
+}
+
 // The DE bucket table of a workgroup: copied from constant memory once, before any wavefront
 // of the workgroup can leave.
 template <int BM, bool MDE, int WORDS>
@@ -990,10 +1497,12 @@ __device__ __forceinline__ void load_de_table(uint32_t *lds_de)
 // The step over one flat buffer.  Full super-tiles: one workgroup per kWaves of them.  TAIL: the
 // ragged end, cut into 2560-element units, one wavefront each.
 template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT>
-__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const StepArgs a)
+__global__ __launch_bounds__(kWaves * 64, (!TAIL && wide_path<BM, BV, B, MDE>()) ? kWideWaves : SOLO_MIN_WAVES)
+void step_kernel(const StepArgs a)
 {
     constexpr int kTile = TAIL ? kTileUnit : tile_elems<BM, BV, B, MDE>();
-    using Lay = SlabLayout<BM, BV, B, MDE, kTile>;
+    constexpr bool kWide = !TAIL && wide_path<BM, BV, B, MDE>();
+    using Lay = SlabLayout<BM, BV, B, MDE, kTile, kWide ? 16 : 8>;
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * Lay::kSlab];
     __shared__ __attribute__((aligned(64))) uint32_t lds_de[Lay::kDeWords];
     load_de_table<BM, MDE, Lay::kDeWords>(lds_de);
@@ -1008,7 +1517,10 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
     const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
     const uint64_t tile = TAIL ? a.tail_tile0 + wave : wg * kWaves + wave;
     if (TAIL ? tile * kTile >= a.n : tile >= a.n_tiles_full) return;
-    step_tile<BM, BV, B, BF16, MDE, TAIL, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
+    if constexpr (kWide)
+        step_tile16<BM, BV, BF16, MDE, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
+    else
+        step_tile<BM, BV, B, BF16, MDE, TAIL, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
 }
 
 // The step over many tensors in one launch.  Every tensor is cut into units of the format's
@@ -1016,10 +1528,13 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void step_kernel(const
 // tile code on a unit that lies inside the tensor and the bounds-checked code on a tensor's
 // ragged last unit.  Blocks never span tensors: each tensor is quantized on its own.
 template <int BM, int BV, int B, bool BF16, bool MDE, bool EXT>
-__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void multi_kernel(const MultiArgs ma)
+__global__ __launch_bounds__(kWaves * 64, (wide_path<BM, BV, B, MDE>() ? kWideWaves : SOLO_MIN_WAVES))
+void multi_kernel(const MultiArgs ma)
 {
     constexpr int kUnit = tile_elems<BM, BV, B, MDE>();
-    using Lay = SlabLayout<BM, BV, B, MDE, kUnit>;
+    constexpr bool kWide = wide_path<BM, BV, B, MDE>();
+    using Lay = SlabLayout<BM, BV, B, MDE, kUnit, kWide ? 16 : 8>;        // the wide slab is the larger one
+    static_assert(Lay::kSlab >= SlabLayout<BM, BV, B, MDE, kUnit, 8>::kSlab, "one slab serves both code paths");
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * Lay::kSlab];
     __shared__ __attribute__((aligned(64))) uint32_t lds_de[Lay::kDeWords];
     load_de_table<BM, MDE, Lay::kDeWords>(lds_de);
@@ -1037,9 +1552,10 @@ __global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES) void multi_kernel(cons
     a.n = e.n; a.index_offset = e.index_offset;
     const uint64_t tile = unit - e.unit0;
     uint32_t *const slab = lds_slab + wave * Lay::kSlab;
-    if ((tile + 1) * kUnit <= a.n)
-        step_tile<BM, BV, B, BF16, MDE, false, EXT, kUnit>(a, tile, lane, slab, lds_de);
-    else
+    if ((tile + 1) * kUnit <= a.n) {
+        if constexpr (kWide) step_tile16<BM, BV, BF16, MDE, EXT, kUnit>(a, tile, lane, slab, lds_de);
+        else step_tile<BM, BV, B, BF16, MDE, false, EXT, kUnit>(a, tile, lane, slab, lds_de);
+    } else
         step_tile<BM, BV, B, BF16, MDE, true, true, kUnit>(a, tile, lane, slab, lds_de);
 }
 
