@@ -1113,14 +1113,14 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
 
     RawPG16<BF16> raw = load_pg16<BF16>(a, tile_e0, lane);
     const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;
-    // Layout transposition through LDS, 16-byte vectors.  Four vectors per lane (fp32): vector i
-    // of the chunk sits in slot i + i / 4, so that both the coalesced side (i = lane + 64 k) and
-    // the lane's own side (i = 4 lane + c, slot 5 lane + c) spread over the banks.  Two vectors
-    // per lane (bf16): slot i + i / 8.
-    static_assert(320 * 4 <= 64 * kColStride16, "staging must fit the column area");
+    // Layout transposition through LDS, 16-byte vectors.  Vector i of the chunk sits in slot
+    // i + i / 8 (one pad vector after every 8): eight neighbouring lanes then cover all banks both
+    // on the coalesced side (i = lane + 64 k) and on the lane's own side (fp32: i = 4 lane + c,
+    // slot 4 lane + lane / 2 + c; bf16: i = 2 lane + c, slot 2 lane + lane / 4 + c).
+    static_assert(288 * 4 <= 64 * kColStride16, "staging must fit the column area");
     float4 *const stage = reinterpret_cast<float4 *>(slab + kOffCol);
-    float4 *const st4_c = stage + (lane + lane / 4u);       // + 80 k
-    float4 *const st4_l = stage + 5u * lane;                // + c
+    float4 *const st4_c = stage + (lane + lane / 8u);       // + 72 k
+    float4 *const st4_l = stage + (4u * lane + lane / 2u);  // + c
     float4 *const st2_c = stage + (lane + lane / 8u);       // + 72 k
     float4 *const st2_l = stage + (2u * lane + lane / 4u);  // + c
 
@@ -1211,10 +1211,11 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         uint32_t mc8[2], vc8[2];
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            const uint32_t mw0 = img_m[wm[r]], mw1 = (BM == 3) ? img_m[wm[r] + 1] : 0u;
-            const uint32_t vw0 = img_v[wv[r]], vw1 = (BV == 3) ? img_v[wv[r] + 1] : 0u;
-            mc8[r] = extract8<BM>(mw0, mw1, sm[r]) & (uint32_t)((1ull << (8 * BM)) - 1ull);
-            vc8[r] = extract8<BV>(vw0, vw1, sv[r]) & (uint32_t)((1ull << (8 * BV)) - 1ull);
+            // (2-bit codes: both runs of the lane lie in one word)
+            const uint32_t mw0 = img_m[wm[BM == 2 ? 0 : r]], mw1 = (BM == 3) ? img_m[wm[r] + 1] : 0u;
+            const uint32_t vw0 = img_v[wv[BV == 2 ? 0 : r]], vw1 = (BV == 3) ? img_v[wv[r] + 1] : 0u;
+            mc8[r] = extract8<BM>(mw0, mw1, BM == 2 ? 8u * r : sm[r]) & (uint32_t)((1ull << (8 * BM)) - 1ull);
+            vc8[r] = extract8<BV>(vw0, vw1, BV == 2 ? 8u * r : sv[r]) & (uint32_t)((1ull << (8 * BV)) - 1ull);
         }
 
         // ---- level tables of this lane's block: entries lig, lig + G
@@ -1237,7 +1238,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         float p[16], g[16];
         {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) st4_c[80 * k] = raw.p[k];
+            for (int k = 0; k < 4; ++k) st4_c[72 * k] = raw.p[k];
             wave_lds_sync();                   // (also orders the level tables before their readers)
             float4 t[4];
 #pragma unroll
@@ -1263,7 +1264,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
             } else {
 #pragma unroll
                 for (int k = 0; k < (BF16 ? 2 : 4); ++k)
-                    st4_c[80 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+                    st4_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
                 wave_lds_sync();
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
@@ -1323,7 +1324,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         {
             float *pp = a.param + (tile_e0 + (uint32_t)it * kIter16) + lane * 4u;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st4_c[80 * k]);
+            for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st4_c[72 * k]);
         }
         wave_lds_sync();                        // the staging area becomes the column area
 
@@ -1397,6 +1398,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         }
 
         // ---- encode and update the state image, one run of 8 elements at a time
+        uint32_t m_word = 0, v_word = 0;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const uint64_t gidx = (a.index_offset + e0 + 8u * r) >> 3;
@@ -1442,18 +1444,27 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
             constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));
             const uint32_t m8 = MDE ? m8_de : ((uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM)));
             const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
-            const uint32_t xm = mc8[r] ^ m8, xv = vc8[r] ^ v8;
+            // 3-bit codes share words between lanes: XOR turns this lane's old fields into the new
+            // ones and leaves the neighbours' alone.  2- and 4-bit words belong to one lane.
             if (BM == 3) {
+                const uint32_t xm = mc8[r] ^ m8;
                 atomicXor(&img_m[wm[r]], (xm << (3u * sm[r])) & 0x3FFFFFFFu);
                 atomicXor(&img_m[wm[r] + 1], (uint32_t)(((uint64_t)xm << (3u * sm[r])) >> 30));
+            } else if (BM == 4) {
+                img_m[wm[r]] = m8;
             } else {
-                atomicXor(&img_m[wm[r]], xm << (BM * sm[r]));
+                m_word |= m8 << (16 * r);
+                if (r == 1) img_m[wm[1]] = m_word;          // (wm[0] has already moved on)
             }
             if (BV == 3) {
+                const uint32_t xv = vc8[r] ^ v8;
                 atomicXor(&img_v[wv[r]], (xv << (3u * sv[r])) & 0x3FFFFFFFu);
                 atomicXor(&img_v[wv[r] + 1], (uint32_t)(((uint64_t)xv << (3u * sv[r])) >> 30));
+            } else if (BV == 4) {
+                img_v[wv[r]] = v8;
             } else {
-                atomicXor(&img_v[wv[r]], xv << (BV * sv[r]));
+                v_word |= v8 << (16 * r);
+                if (r == 1) img_v[wv[1]] = v_word;
             }
             wm[r] += kIter16 / CM; sm[r] += kIter16 % CM;
             if (sm[r] >= (uint32_t)CM) { sm[r] -= CM; wm[r] += 1; }

@@ -266,6 +266,20 @@ def test_all_formats(so, gpu, bm, bv):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
 
 
+@pytest.mark.parametrize("bm,bv,de", [(2, 2, False), (2, 3, False), (2, 4, False), (3, 2, False), (4, 2, False),
+                                      (2, 2, True), (2, 3, True), (2, 4, True), (3, 2, True)])
+def test_wide_path_formats(so, gpu, bm, bv, de):
+    """The formats whose full super-tiles of 128-element blocks run 16 elements per lane: both
+    gradient types, the plain step and the one with every extra, four full tiles and a ragged end
+    (which runs the 8-elements-per-lane code on the same state)."""
+    n = 4 * TILE + 3000
+    for bf16 in (True, False):
+        run_teacher_forced(so, gpu, n, bm, bv, 128, bf16=bf16, steps=3, seed0=900 + 10 * bm + bv, de=de,
+                           std=1e-4 if bf16 else 1e-3, kind="normal_outliers" if bf16 else "student_t3")
+        run_free(so, gpu, n, bm, bv, 128, bf16=bf16, steps=5, seed0=950 + 10 * bm + bv, de=de,
+                 optimizer="adabelief", grad_scale=0.5, bf16_copy=True, eps=1e-12)
+
+
 # ------------------------------------------------- variants of the step (one fused pass each)
 
 @pytest.mark.parametrize("optimizer", ("adamw", "adam_l2", "adabelief"))
