@@ -482,6 +482,7 @@ __device__ __forceinline__ void wave_lds_sync()
 // registers):
 //   columns   64 x 12 words  per-lane sorted keys + sentinel; doubles as the staging area of
 //                            the layout transposition at the start of an iteration
+//                            (E = 16, the wide path: 64 x 20 words)
 //   img_m/v   the super-tile's code words (loaded once, updated in place, written back once)
 //   tv, tm    level tables of the blocks of the current iteration
 //   sc        3 block scalars (Delta_m, Delta_v, alpha) per block of the super-tile
@@ -499,10 +500,7 @@ struct SlabLayout {
     static constexpr int kOffTv = ((kOffImgV + VW + 4 + 15) / 16) * 16;      // 64-byte aligned
     static constexpr int kOffTm = kOffTv + ((NG * VT + 15) / 16) * 16;
     static constexpr int kOffSc = kOffTm + NG * MTS;
-#ifndef SOLO_PAD_SLAB
-#define SOLO_PAD_SLAB 0
-#endif
-    static constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16 + SOLO_PAD_SLAB;
+    static constexpr int kSlab = ((kOffSc + 3 * NBT + 15) / 16) * 16;
     static constexpr bool kDeTable = MDE && BM >= 3;     // DE rounding by bucket table (two boundaries: compares are cheaper)
     static constexpr int kDeWords = kDeTable ? 4 * DeBuckets<BM>::N : 16;
     static constexpr int kBytesPerWg = 4 * (kWaves * kSlab + kDeWords);
