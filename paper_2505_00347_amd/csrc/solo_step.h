@@ -66,7 +66,7 @@ static_assert(kWaves >= 2, "the ragged end of a flat buffer is launched as up to
 constexpr int kXcds = 8;           // accelerator dies of an MI355X (each has its own L2)
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
 constexpr int kIter16 = 1024;      // elements per iteration of the wide path (64 lanes x 16)
-constexpr int kColStride16 = 20;   // its column stride (16 keys, +inf, pad)
+constexpr int kColStride16 = 18;   // its column stride (16 keys, +inf, pad; columns are written 8 bytes at a time)
 constexpr int kWideWaves = 4;      // wavefronts per SIMD the wide path is compiled for
 constexpr float kTiny = 0x1p-100f; // block maxima below this are stored as 0
 constexpr float kRhoMin = 0x1p-64f;
@@ -482,7 +482,7 @@ __device__ __forceinline__ void wave_lds_sync()
 // registers):
 //   columns   64 x 12 words  per-lane sorted keys + sentinel; doubles as the staging area of
 //                            the layout transposition at the start of an iteration
-//                            (E = 16, the wide path: 64 x 20 words)
+//                            (E = 16, the wide path: 64 x 18 words)
 //   img_m/v   the super-tile's code words (loaded once, updated in place, written back once)
 //   tv, tm    level tables of the blocks of the current iteration
 //   sc        3 block scalars (Delta_m, Delta_v, alpha) per block of the super-tile
@@ -1341,8 +1341,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
             sort16(key);
             col[16] = kInfBits;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                *reinterpret_cast<uint4 *>(col + 4 * c) = make_uint4(key[4 * c], key[4 * c + 1], key[4 * c + 2], key[4 * c + 3]);
+            for (int c = 0; c < 8; ++c) *reinterpret_cast<uint2 *>(col + 2 * c) = make_uint2(key[2 * c], key[2 * c + 1]);
             uint32_t head = key[0], behind = key[1], haddr = col_addr;
             for (uint32_t k = 0; k < a.rank_full; ++k) {
                 const uint32_t mn = group_reduce<G>(head, UMin());

@@ -266,8 +266,9 @@ def test_all_formats(so, gpu, bm, bv):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
 
 
-@pytest.mark.parametrize("bm,bv,de", [(2, 2, False), (2, 3, False), (2, 4, False), (3, 2, False), (4, 2, False),
-                                      (2, 2, True), (2, 3, True), (2, 4, True), (3, 2, True)])
+@pytest.mark.parametrize("bm,bv,de", [(2, 2, False), (2, 3, False), (2, 4, False), (3, 2, False), (3, 3, False),
+                                      (4, 2, False), (2, 2, True), (2, 3, True), (2, 4, True), (3, 2, True),
+                                      (3, 3, True), (4, 2, True)])
 def test_wide_path_formats(so, gpu, bm, bv, de):
     """The formats whose full super-tiles of 128-element blocks run 16 elements per lane: both
     gradient types, the plain step and the one with every extra, four full tiles and a ragged end
