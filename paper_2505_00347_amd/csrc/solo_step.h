@@ -1181,14 +1181,6 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
     float *const my_tm = reinterpret_cast<float *>(slab + kOffTm) + grp * MTS;
     const uint32_t tv_addr = lds_addr(my_tv), tm_addr = lds_addr(my_tm);
     const uint32_t col_addr = lds_addr(col);
-    // word and slot of the first code of the lane's two runs of 8 in iteration 0; an iteration
-    // advances every stream by 1024 codes
-    uint32_t wm[2], sm[2], wv[2], sv[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        wm[r] = (lane * 16u + 8u * r) / CM; sm[r] = (lane * 16u + 8u * r) % CM;
-        wv[r] = (lane * 16u + 8u * r) / CV; sv[r] = (lane * 16u + 8u * r) % CV;
-    }
 
     float de_level[(16 + G - 1) / G];
     uint32_t de_base = 0;
@@ -1203,6 +1195,17 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         const uint32_t e_loc = (uint32_t)it * kIter16 + lane * 16u;
         const uint64_t e0 = tile_e0 + e_loc;
         const uint32_t bl = (uint32_t)it * NG + grp;
+        // word and slot of the first code of the lane's two runs of 8 (recomputed in every
+        // iteration: cheaper in registers than carrying them; e / 10 by multiplication, exact far
+        // beyond the tile size)
+        static_assert(kTile <= 20480, "range of the division by 10");
+        uint32_t wm[2], sm[2], wv[2], sv[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const uint32_t e = e_loc + 8u * r;
+            wm[r] = (CM == 10) ? (e * 52429u) >> 19 : e / CM; sm[r] = e - wm[r] * CM;
+            wv[r] = (CV == 10) ? (e * 52429u) >> 19 : e / CV; sv[r] = e - wv[r] * CV;
+        }
 
         // ---- old state of the block and of this lane's elements (LDS)
         const float dm_old = sc[bl], dv_old = sc[NBT + bl], al_old = sc[2 * NBT + bl];
@@ -1451,7 +1454,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
                 img_m[wm[r]] = m8;
             } else {
                 m_word |= m8 << (16 * r);
-                if (r == 1) img_m[wm[1]] = m_word;          // (wm[0] has already moved on)
+                if (r == 1) img_m[wm[0]] = m_word;
             }
             if (BV == 3) {
                 const uint32_t xv = vc8[r] ^ v8;
@@ -1461,12 +1464,8 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
                 img_v[wv[r]] = v8;
             } else {
                 v_word |= v8 << (16 * r);
-                if (r == 1) img_v[wv[1]] = v_word;
+                if (r == 1) img_v[wv[0]] = v_word;
             }
-            wm[r] += kIter16 / CM; sm[r] += kIter16 % CM;
-            if (sm[r] >= (uint32_t)CM) { sm[r] -= CM; wm[r] += 1; }
-            wv[r] += kIter16 / CV; sv[r] += kIter16 % CV;
-            if (sv[r] >= (uint32_t)CV) { sv[r] -= CV; wv[r] += 1; }
         }
         if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
     }
