@@ -149,7 +149,7 @@ def main():
                     help="flat: one call over the whole flat buffer (the metric); multi: the workload's "
                          "tensors as separate buffers in one solo_adamw_step_multi launch; per_tensor: one "
                          "solo_adamw_step call per tensor")
-    ap.add_argument("--placements", type=int, default=3,
+    ap.add_argument("--placements", type=int, default=5,
                     help="allocate the workload this many times and keep the allocation on which the "
                          "warm-up steps ran fastest (1: take the first allocation as it comes)")
     args = ap.parse_args()
@@ -240,7 +240,11 @@ def main():
     # the workload up to --placements times, warm each up, keep the fastest, free the others.
     cands, trial_ms = [], []
     trials = max(args.warmup, 2) if args.placements > 1 else args.warmup
-    for _ in range(max(1, args.placements)):
+    for k in range(max(1, args.placements)):
+        if k:                                    # every candidate stays allocated until the choice is made
+            free_b, total_b = torch.cuda.mem_get_info()
+            if free_b < (total_b - free_b) / k + (8 << 30):
+                break
         r = Resident()
         ms = r.run(trials)
         cands.append(r)
