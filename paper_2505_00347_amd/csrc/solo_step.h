@@ -14,10 +14,10 @@
 // step_tile() is the whole step for one super-tile; step_kernel runs it over
 // a flat buffer (full tiles, and the ragged end with bounds checks),
 // multi_kernel over the tensors of a caller-built table.  Full super-tiles of
-// formats with 128-element blocks whose state image is small enough take
-// step_tile16() instead: 16 elements per lane, 8 lanes per block, 1024
-// elements per iteration, four wavefronts per SIMD instead of five (fewer
-// instructions per element; see there).
+// formats whose state image is small enough take step_tile16() instead: 16
+// elements per lane, 8 (4) lanes per block, 1024 elements per iteration, four
+// wavefronts per SIMD instead of five (fewer instructions per element; see
+// there).
 //
 // The kernel is bound by vector-ALU issue as much as by HBM (packed FP32 is
 // off, so a CU retires 64 lane-operations per clock: about 80 per parameter at
@@ -140,7 +140,7 @@ __device__ __forceinline__ uint32_t dpp(uint32_t x)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
 }
 
-// Butterfly over the G (8 or 16) lanes that hold one block: lane^1 and lane^2
+// Butterfly over the G (4, 8 or 16) lanes that hold one block: lane^1 and lane^2
 // by quad permutes, then mirror inside the half row, then inside the row.
 // Every lane ends with the result of its whole group.
 template <int G, typename Op>
@@ -148,7 +148,7 @@ __device__ __forceinline__ uint32_t group_reduce(uint32_t x, Op op)
 {
     x = op(x, dpp<0xB1>(x));    // quad_perm [1,0,3,2]
     x = op(x, dpp<0x4E>(x));    // quad_perm [2,3,0,1]
-    x = op(x, dpp<0x141>(x));   // row_half_mirror
+    if (G >= 8) x = op(x, dpp<0x141>(x));   // row_half_mirror
     if (G == 16) x = op(x, dpp<0x140>(x));  // row_mirror
     return x;
 }
@@ -244,15 +244,15 @@ __device__ __noinline__ uint32_t walk_base(uint32_t y, float rho)
 // The base alpha = rho^(1/K) as stored: the largest binary32 whose last level does not exceed rho.
 // The hardware exp2/log2 give a guess that is a few units in the last place off; the lanes of the
 // group test the 16 consecutive binary32 values yb - 8 .. yb + 7 around it in parallel (one per
-// lane in a group of 16, two per lane in a group of 8) and count those that fit.  Only a guess
+// lane in a group of 16, two or four per lane in a group of 8 or 4) and count those that fit.  Only a guess
 // further off than that takes the bounded walk.  Returns the bit pattern; meaningful if rho < 1.
 template <int BV, int G>
 __device__ __forceinline__ uint32_t search_base(float rho, bool need, uint32_t lane, uint32_t lig, uint32_t gshift)
 {
     constexpr int K = (1 << BV) - 1;
     constexpr float invK = 1.0f / (float)K;
-    constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
-    static_assert(G == 8 || G == 16, "group of 8 or 16 lanes");
+    constexpr uint32_t GMASK = (1u << G) - 1u;
+    static_assert(G == 4 || G == 8 || G == 16, "group of 4, 8 or 16 lanes");
     const float y0 = __builtin_amdgcn_exp2f(__builtin_amdgcn_logf(rho) * invK);
     const uint32_t yb = umed3(f2u(y0), 0x00800000u, kOneBits);
     uint32_t cnt;
@@ -260,11 +260,14 @@ __device__ __forceinline__ uint32_t search_base(float rho, bool need, uint32_t l
         const uint32_t cand = umin(yb + lig - 8u, kOneBits);
         const bool fits = last_level<BV>(u2f(cand)) <= rho;
         cnt = (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits), lane, gshift, GMASK));
-    } else {
-        const uint32_t cand0 = umin(yb + lig - 8u, kOneBits), cand1 = umin(yb + lig, kOneBits);
-        const bool fits0 = last_level<BV>(u2f(cand0)) <= rho, fits1 = last_level<BV>(u2f(cand1)) <= rho;
-        cnt = (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits0), lane, gshift, GMASK)) +
-              (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits1), lane, gshift, GMASK));
+    } else {                                   // 16 / G candidates per lane
+        cnt = 0;
+#pragma unroll
+        for (int c = 0; c < 16 / G; ++c) {
+            const uint32_t cand = umin(yb + lig + (uint32_t)(c * G) - 8u, kOneBits);
+            const bool fits = last_level<BV>(u2f(cand)) <= rho;
+            cnt += (uint32_t)__builtin_popcount(group_bits(__builtin_amdgcn_ballot_w64(fits), lane, gshift, GMASK));
+        }
     }
     uint32_t ab = umin(yb + cnt - 9u, kOneBits);
     // not bracketed (all or none of the candidates fit): walk from the nearest end
@@ -510,15 +513,18 @@ struct SlabLayout {
 // arguments, first loads) over more work, so the tile is doubled wherever the larger state
 // image still leaves room for SOLO_MIN_WAVES wavefronts per SIMD.
 // The wide path (16 elements per lane, see step_tile16) serves the full super-tiles of a format
-// with 128-element blocks whenever its larger LDS slab lets kWideWaves wavefronts per SIMD run.
+// whenever its larger LDS slab lets kWideWaves wavefronts per SIMD run.
 #ifndef SOLO_WIDE
 #define SOLO_WIDE 1
+#endif
+#ifndef SOLO_WIDE_B64
+#define SOLO_WIDE_B64 1
 #endif
 template <int BM, int BV, int B, bool MDE>
 constexpr bool wide_path()
 {
     constexpr int wgs = kWideWaves * 4 / kWaves;
-    return SOLO_WIDE && B == 128 && SlabLayout<BM, BV, 128, MDE, 2 * kTileUnit, 16>::kBytesPerWg * wgs <= kLdsPerCu;
+    return SOLO_WIDE && (SOLO_WIDE_B64 || B == 128) && SlabLayout<BM, BV, B, MDE, 2 * kTileUnit, 16>::kBytesPerWg * wgs <= kLdsPerCu;
 }
 
 template <int BM, int BV, int B, bool MDE>
@@ -1071,19 +1077,19 @@ __device__ __forceinline__ RawPG16<BF16> load_pg16(const StepArgs &a, uint64_t c
     return r;
 }
 
-// The wide path: the same step as step_tile() for a full super-tile of 128-element blocks, with
-// 16 consecutive elements per lane and 1024 per iteration.  A block is held by 8 lanes, so the
+// The wide path: the same step as step_tile() for a full super-tile, with 16 consecutive
+// elements per lane and 1024 per iteration.  A block is held by 8 lanes (4 for B = 64), so the
 // work that is done once per lane and block (level tables, the division, the base, the hash,
 // packing) is spread over twice as many elements, a group reduction is three DPP steps instead
 // of four, and a block still needs only r extraction rounds.  The price is registers (four
 // wavefronts per SIMD instead of five) and a 16-key sort per lane.
-template <int BM, int BV, bool BF16, bool MDE, bool EXT, int TILE>
+template <int BM, int BV, int B, bool BF16, bool MDE, bool EXT, int TILE>
 __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t tile, const uint32_t lane,
                                             uint32_t *const slab, const uint32_t *const lds_de)
 {
-    constexpr int B = 128, E = 16;
-    constexpr int G = B / E;                       // lanes per block (8)
-    constexpr int NG = 64 / G;                     // blocks per iteration (8)
+    constexpr int E = 16;
+    constexpr int G = B / E;                       // lanes per block (8; 4 for 64-element blocks)
+    constexpr int NG = 64 / G;                     // blocks per iteration (8; 16)
     constexpr int kTile = TILE;
     constexpr int kIters = kTile / kIter16;
     static_assert(kTile % kIter16 == 0, "whole iterations");
@@ -1096,7 +1102,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
     constexpr int VT = K + 1;
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
     constexpr int MTS = Lay::MTS;
-    constexpr uint32_t GMASK = 0xFFu;
+    constexpr uint32_t GMASK = (1u << G) - 1u;
     constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
     constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
     constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
@@ -1525,7 +1531,7 @@ void step_kernel(const StepArgs a)
     const uint64_t tile = TAIL ? a.tail_tile0 + wave : wg * kWaves + wave;
     if (TAIL ? tile * kTile >= a.n : tile >= a.n_tiles_full) return;
     if constexpr (kWide)
-        step_tile16<BM, BV, BF16, MDE, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
+        step_tile16<BM, BV, B, BF16, MDE, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
     else
         step_tile<BM, BV, B, BF16, MDE, TAIL, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
 }
@@ -1560,7 +1566,7 @@ void multi_kernel(const MultiArgs ma)
     const uint64_t tile = unit - e.unit0;
     uint32_t *const slab = lds_slab + wave * Lay::kSlab;
     if ((tile + 1) * kUnit <= a.n) {
-        if constexpr (kWide) step_tile16<BM, BV, BF16, MDE, EXT, kUnit>(a, tile, lane, slab, lds_de);
+        if constexpr (kWide) step_tile16<BM, BV, B, BF16, MDE, EXT, kUnit>(a, tile, lane, slab, lds_de);
         else step_tile<BM, BV, B, BF16, MDE, false, EXT, kUnit>(a, tile, lane, slab, lds_de);
     } else
         step_tile<BM, BV, B, BF16, MDE, true, true, kUnit>(a, tile, lane, slab, lds_de);

@@ -266,18 +266,22 @@ def test_all_formats(so, gpu, bm, bv):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
 
 
-@pytest.mark.parametrize("bm,bv,de", [(2, 2, False), (2, 3, False), (2, 4, False), (3, 2, False), (3, 3, False),
-                                      (4, 2, False), (2, 2, True), (2, 3, True), (2, 4, True), (3, 2, True),
-                                      (3, 3, True), (4, 2, True)])
-def test_wide_path_formats(so, gpu, bm, bv, de):
-    """The formats whose full super-tiles of 128-element blocks run 16 elements per lane: both
-    gradient types, the plain step and the one with every extra, four full tiles and a ragged end
-    (which runs the 8-elements-per-lane code on the same state)."""
+WIDE_FORMATS = [(bm, bv, 128, de) for de in (False, True)
+                for bm, bv in ((2, 2), (2, 3), (2, 4), (3, 2), (3, 3), (4, 2))] + \
+               [(bm, bv, 64, de) for de in (False, True) for bm, bv in ((2, 2), (2, 3), (3, 2))]
+
+
+@pytest.mark.parametrize("bm,bv,B,de", WIDE_FORMATS)
+def test_wide_path_formats(so, gpu, bm, bv, B, de):
+    """The formats whose full super-tiles run 16 elements per lane (8 lanes per 128-element
+    block, 4 per 64-element block): both gradient types, the plain step and the one with every
+    extra, four full tiles and a ragged end (which runs the 8-elements-per-lane code on the same
+    state)."""
     n = 4 * TILE + 3000
     for bf16 in (True, False):
-        run_teacher_forced(so, gpu, n, bm, bv, 128, bf16=bf16, steps=3, seed0=900 + 10 * bm + bv, de=de,
+        run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=900 + 10 * bm + bv, de=de,
                            std=1e-4 if bf16 else 1e-3, kind="normal_outliers" if bf16 else "student_t3")
-        run_free(so, gpu, n, bm, bv, 128, bf16=bf16, steps=5, seed0=950 + 10 * bm + bv, de=de,
+        run_free(so, gpu, n, bm, bv, B, bf16=bf16, steps=5, seed0=950 + 10 * bm + bv, de=de,
                  optimizer="adabelief", grad_scale=0.5, bf16_copy=True, eps=1e-12)
 
 
