@@ -548,6 +548,227 @@ inline int unit_elems(uint32_t bits_m, uint32_t bits_v, uint32_t block_size, boo
     return 0;
 }
 
+// ---- pieces shared by the two tile functions
+
+// Stages a full super-tile's state in LDS (coalesced, 16 bytes per lane): every load is issued
+// before the first one is waited for, one memory round trip instead of five.
+template <int BM, int BV, int MW, int VW, int NBT>
+__device__ __forceinline__ void load_state_image(const StepArgs &a, uint64_t tile, uint32_t lane,
+                                                 uint32_t *img_m, uint32_t *img_v, float *sc)
+{
+    static_assert(MW % 4 == 0 && VW % 4 == 0, "128-bit staging");
+    constexpr int RM = (MW / 4 + 63) / 64, RV = (VW / 4 + 63) / 64, RS = (NBT + 63) / 64;
+    const u32x4_t *gm = reinterpret_cast<const u32x4_t *>(a.m_words + tile * MW);
+    const u32x4_t *gv = reinterpret_cast<const u32x4_t *>(a.v_words + tile * VW);
+    u32x4_t xm[RM], xv[RV];
+    float s_dm[RS], s_dv[RS], s_al[RS];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        const uint32_t q = lane + 64u * r;
+        if (q < MW / 4) xm[r] = __builtin_nontemporal_load(gm + q);
+    }
+#pragma unroll
+    for (int r = 0; r < RV; ++r) {
+        const uint32_t q = lane + 64u * r;
+        if (q < VW / 4) xv[r] = __builtin_nontemporal_load(gv + q);
+    }
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        const uint32_t bb = lane + 64u * r;
+        if (bb < NBT) {
+            const uint64_t gb = tile * NBT + bb;
+            s_dm[r] = a.m_scale[gb]; s_dv[r] = a.v_scale[gb]; s_al[r] = a.v_base[gb];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        const uint32_t q = lane + 64u * r;
+        if (q < MW / 4) {
+            if (BM == 3) xm[r] &= 0x3FFFFFFFu;
+            *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = xm[r];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RV; ++r) {
+        const uint32_t q = lane + 64u * r;
+        if (q < VW / 4) {
+            if (BV == 3) xv[r] &= 0x3FFFFFFFu;
+            *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = xv[r];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        const uint32_t bb = lane + 64u * r;
+        if (bb < NBT) { sc[bb] = s_dm[r]; sc[NBT + bb] = s_dv[r]; sc[2 * NBT + bb] = s_al[r]; }
+    }
+}
+
+// Writes a full super-tile's state back (coalesced, streamed).
+template <int MW, int VW, int NBT>
+__device__ __forceinline__ void store_state_image(const StepArgs &a, uint64_t tile, uint32_t lane,
+                                                  const uint32_t *img_m, const uint32_t *img_v, const float *sc)
+{
+    u32x4_t *gm = reinterpret_cast<u32x4_t *>(a.m_words + tile * MW);
+    u32x4_t *gv = reinterpret_cast<u32x4_t *>(a.v_words + tile * VW);
+    for (uint32_t q = lane; q < MW / 4; q += 64)
+        stream_store_u4(gm + q, *reinterpret_cast<const u32x4_t *>(img_m + 4 * q));
+    for (uint32_t q = lane; q < VW / 4; q += 64)
+        stream_store_u4(gv + q, *reinterpret_cast<const u32x4_t *>(img_v + 4 * q));
+    for (uint32_t b = lane; b < NBT; b += 64) {
+        const uint64_t gb = tile * NBT + b;
+        a.m_scale[gb] = sc[b];
+        a.v_scale[gb] = sc[NBT + b];
+        a.v_base[gb] = sc[2 * NBT + b];
+    }
+}
+
+// The r-th smallest key of every group of G lanes (full blocks).  Each lane has parked its sorted
+// column at col_addr (the +inf sentinel behind it) and passes its two smallest keys.  A round:
+// group minimum of the heads by DPP; the lane that holds it pops its column.  The pop is written
+// out (the holders run under their own exec mask), so a round is straight-line code with the
+// loop's back edge as its only branch.  A lane keeps the key behind its head in a register: a pop
+// moves it up and fetches the one after it, whose LDS latency then lies outside the chain of
+// rounds (it is waited for only when the same lane pops again).  A scalar population count
+// detects the rounds in which two lanes of a group tie; then only the lowest holder pops, so
+// exactly one key leaves a group per round.
+template <int G>
+__device__ __forceinline__ uint32_t extract_rth(uint32_t head, uint32_t behind, uint32_t haddr, uint32_t rank)
+{
+    constexpr int NG = 64 / G;
+    constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : (1u << (G & 15)) - 1u;
+    uint32_t xp_bits = 0;
+    for (uint32_t k = 0; k < rank; ++k) {
+        const uint32_t mn = group_reduce<G>(head, UMin());
+        uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
+        if (__builtin_expect(__builtin_popcountll(holders) != NG, 0)) {
+            uint64_t lowest = 0;
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+                const uint64_t f = (holders >> (gi * G)) & (uint64_t)GMASK;
+                lowest |= (f & (0 - f)) << (gi * G);
+            }
+            holders = lowest;
+        }
+        xp_bits = mn;
+        uint64_t saved;
+        asm volatile("s_mov_b64 %[saved], exec\n\t"
+                     "s_mov_b64 exec, %[holders]\n\t"
+                     "s_waitcnt lgkmcnt(0)\n\t"
+                     "v_mov_b32_e32 %[head], %[behind]\n\t"
+                     "ds_read_b32 %[behind], %[haddr] offset:8\n\t"
+                     "v_add_u32_e32 %[haddr], 4, %[haddr]\n\t"
+                     "s_mov_b64 exec, %[saved]"
+                     : [head] "+v"(head), [behind] "+v"(behind), [haddr] "+v"(haddr), [saved] "=&s"(saved)
+                     : [holders] "s"(holders)
+                     : "memory");
+    }
+    // the last fetch may still be in flight: its register is free only once it has landed
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(behind) : : "memory");
+    return xp_bits;
+}
+
+// Per-block constants of the two encoders, from the new block statistics.
+struct BlockCodec {
+    float inv_s;     // L / Delta_m (DE: 1 / Delta_m); 0 for an all-zero block
+    float alpha;     // the stored base; 1 for a degenerate block
+    float inv_l2a;   // 1 / log2(alpha); 0 for a degenerate block
+    float rdv;       // 1 / Delta_v;      0 for a degenerate block (with bias 1 the ratio is then 1)
+    float bias;
+};
+
+// rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes) share one IEEE division, then a
+// quad permute hands every lane both; alpha by search_base.
+template <int BV, int G, int L, bool MDE>
+__device__ __forceinline__ BlockCodec block_codec(uint32_t xp_bits, float dm, float dv, uint32_t lane,
+                                                  uint32_t lig, uint32_t gshift)
+{
+    const float num = (lane & 1u) ? (MDE ? 1.0f : (float)L) : u2f(xp_bits);
+    const float den = (lane & 1u) ? dm : dv;
+    const float quo = num / den;
+    float rho = u2f(dpp<0xA0>(f2u(quo)));        // quad_perm [0,0,2,2]
+    float inv_s = u2f(dpp<0xF5>(f2u(quo)));      // quad_perm [1,1,3,3]
+    inv_s = dm > 0.0f ? inv_s : 0.0f;
+    rho = dv > 0.0f ? rho : 1.0f;
+    rho = rho < kRhoMin ? kRhoMin : rho;
+    BlockCodec c = {inv_s, 1.0f, 0.0f, 0.0f, 1.0f};
+    const bool need = rho < 1.0f;
+    const uint32_t ab = search_base<BV, G>(rho, need, lane, lig, gshift);
+    if (need) {
+        c.alpha = u2f(ab);
+        c.inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(c.alpha));
+        c.rdv = __builtin_amdgcn_rcpf(dv);
+        c.bias = 0.0f;
+    }
+    return c;
+}
+
+// Encodes a lane's run of 8 consecutive elements starting at global element index e (a multiple
+// of 8): returns the packed 1st- and 2nd-moment codes (element j in bits [b j, b j + b)).
+// xi: one hashed start and stride per 8 elements; 1.5 + xi - 2^-24 is built as a float in [1,2)
+// by one bit-align of the hashed word.  Codes are rounded in the float domain, four to an
+// accumulator: m: code - L = rint(m^ * L/Delta_m) in [-L, L];
+// v: code + 1 = floor(log_alpha(v^/Delta_v) + 1.5 + xi).  `ok` (TAIL only): the elements that exist.
+template <int BM, int BV, bool MDE, bool TAIL>
+__device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const float *mh, const float *vh,
+                                           const bool *ok, const BlockCodec &c, uint32_t de_base,
+                                           uint32_t &m8, uint32_t &v8)
+{
+    constexpr int L = (1 << (BM - 1)) - 1;
+    constexpr int K = (1 << BV) - 1;
+    constexpr bool kDeTable = MDE && BM >= 3;
+    const uint64_t gidx = (a.index_offset + e) >> 3;
+    uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
+    uint32_t Y = mix32(X ^ a.key1) | 1u;
+    if (!a.stochastic) { X = 0x80000000u; Y = 0u; }     // xi = 0: the float is 1.5
+    uint32_t xj = X + ((Y << 3) - Y);                   // X + j Y, walked down from j = 7
+    float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
+    uint32_t m8_de = 0;
+#pragma unroll
+    for (int j = 7; j >= 0; --j, xj -= Y) {
+        float tm = 0.0f;
+        if (!MDE) {
+            tm = __builtin_rintf(mh[j] * c.inv_s);
+        } else {
+            // DE: nearest level on the magnitude; inv_s = 1/Delta_m
+            const float z = mh[j] * c.inv_s;
+            uint32_t code;
+            if (kDeTable) {
+                // entry of the bucket of |z| (16 bytes per bucket: z >= 0, then z < 0)
+                // (clamped on both sides: a non-finite input must not leave the table)
+                const uint32_t bk = umin(umax(__builtin_amdgcn_ubfe(f2u(z), 21u, 10u), DeBuckets<BM>::kLo),
+                                         DeBuckets<BM>::kHi);
+                const uint32_t addr = ((f2u(z) >> 28) & 8u) | ((bk << 4) + de_base);
+                const u32x2_t en = *(lds_u32x2_t *)(uintptr_t)addr;
+                code = en.y + (z > u2f(en.x) ? 1u : 0u);
+            } else {
+                // few levels: the code is the number of rounding boundaries below z.  A value
+                // on a boundary keeps the level of smaller magnitude: '>' on the positive side,
+                // '>=' on the negative one (z = -0 is above every negative boundary: code L).
+                code = 0;
+#pragma unroll
+                for (int k = 0; k < L; ++k) code += (z >= -DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
+#pragma unroll
+                for (int k = 0; k <= L; ++k) code += (z > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
+            }
+            if (TAIL && !ok[j]) code = 0;
+            m8_de |= code << (BM * j);
+        }
+        const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, xj, 9u));
+        const float ratio = __builtin_fmaf(vh[j], c.rdv, c.bias);
+        float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), c.inv_l2a, f));
+        tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));   // +inf (v^ = 0) takes the last code
+        if (TAIL && !ok[j]) { tm = -(float)L; tv = 1.0f; }
+        if (j == 7)      { am_hi = tm; av_hi = tv; }
+        else if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
+        else if (j == 3) { am_lo = tm; av_lo = tv; }
+        else             { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
+    }
+    constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));   // L * sum 2^(BM j), j < 4
+    constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
+    m8 = MDE ? m8_de : ((uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM)));
+    v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
+}
+
 // One super-tile of TILE elements, processed by the calling wavefront: the whole step for the
 // elements [tile * TILE, (tile + 1) * TILE) of the buffers in `a` (TAIL: clipped to a.n, with
 // bounds checks on every element).  `slab` is this wavefront's LDS, `lds_de` the workgroup's DE
@@ -599,53 +820,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     float4 *const st_l = stage + (2u * lane + lane / 4u);   // this lane's 8 elements: st_l[0], st_l[1]
 
     // ---- stage the super-tile's state in LDS (coalesced; full tiles move 16 bytes per lane)
-    static_assert(MW % 4 == 0 && VW % 4 == 0 && kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
+    static_assert(kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
     if (!TAIL) {
-        // every load is issued before the first one is waited for: one memory round trip, not five
-        constexpr int RM = (MW / 4 + 63) / 64, RV = (VW / 4 + 63) / 64, RS = (NBT + 63) / 64;
-        const u32x4_t *gm = reinterpret_cast<const u32x4_t *>(a.m_words + tile * MW);
-        const u32x4_t *gv = reinterpret_cast<const u32x4_t *>(a.v_words + tile * VW);
-        u32x4_t xm[RM], xv[RV];
-        float s_dm[RS], s_dv[RS], s_al[RS];
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < MW / 4) xm[r] = __builtin_nontemporal_load(gm + q);
-        }
-#pragma unroll
-        for (int r = 0; r < RV; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < VW / 4) xv[r] = __builtin_nontemporal_load(gv + q);
-        }
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            const uint32_t bb = lane + 64u * r;
-            if (bb < NBT) {
-                const uint64_t gb = tile * NBT + bb;
-                s_dm[r] = a.m_scale[gb]; s_dv[r] = a.v_scale[gb]; s_al[r] = a.v_base[gb];
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < MW / 4) {
-                if (BM == 3) xm[r] &= 0x3FFFFFFFu;
-                *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = xm[r];
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < RV; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < VW / 4) {
-                if (BV == 3) xv[r] &= 0x3FFFFFFFu;
-                *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = xv[r];
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            const uint32_t bb = lane + 64u * r;
-            if (bb < NBT) { sc[bb] = s_dm[r]; sc[NBT + bb] = s_dv[r]; sc[2 * NBT + bb] = s_al[r]; }
-        }
+        load_state_image<BM, BV, MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
     } else {
         for (uint32_t w = lane; w < MW; w += 64) {
             const uint64_t gw = tile * MW + w;
@@ -863,122 +1040,16 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             }
         };
         if (!TAIL) {
-            // Full tiles: the pop is written out (run the holders under their own exec mask), so
-            // that a round is straight-line code with the loop's back edge as its only branch.
-            // A lane keeps the key behind its head in a register: a pop moves it up and fetches
-            // the one after it, whose LDS latency then lies outside the chain of rounds (it is
-            // waited for only when the same lane pops again).
-            uint32_t behind = key[1];
-            for (uint32_t k = 0; k < a.rank_full; ++k) {
-                const uint32_t mn = group_reduce<G>(head, UMin());
-                uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
-                if (__builtin_expect(__builtin_popcountll(holders) != NG, 0)) {
-                    uint64_t lowest = 0;           // a tie: the lowest holder of each group pops
-#pragma unroll
-                    for (int gi = 0; gi < NG; ++gi) {
-                        const uint64_t f = (holders >> (gi * G)) & (uint64_t)GMASK;
-                        lowest |= (f & (0 - f)) << (gi * G);
-                    }
-                    holders = lowest;
-                }
-                xp_bits = mn;
-                uint64_t saved;
-                asm volatile("s_mov_b64 %[saved], exec\n\t"
-                             "s_mov_b64 exec, %[holders]\n\t"
-                             "s_waitcnt lgkmcnt(0)\n\t"
-                             "v_mov_b32_e32 %[head], %[behind]\n\t"
-                             "ds_read_b32 %[behind], %[haddr] offset:8\n\t"
-                             "v_add_u32_e32 %[haddr], 4, %[haddr]\n\t"
-                             "s_mov_b64 exec, %[saved]"
-                             : [head] "+v"(head), [behind] "+v"(behind), [haddr] "+v"(haddr), [saved] "=&s"(saved)
-                             : [holders] "s"(holders)
-                             : "memory");
-            }
-            // the last fetch may still be in flight: its register is free only once it has landed
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(behind) : : "memory");
+            xp_bits = extract_rth<G>(key[0], key[1], col_addr, a.rank_full);
         } else {
             for (uint32_t k = 0; k < a.rank_full; ++k) extract_round(k);
         }
 
-        // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
-        const float num = (lane & 1u) ? (MDE ? 1.0f : (float)L) : u2f(xp_bits);
-        const float den = (lane & 1u) ? dm : dv;
-        const float quo = num / den;
-        float rho = u2f(dpp<0xA0>(f2u(quo)));        // quad_perm [0,0,2,2]
-        float inv_s = u2f(dpp<0xF5>(f2u(quo)));      // quad_perm [1,1,3,3]
-        inv_s = dm > 0.0f ? inv_s : 0.0f;
-        rho = dv > 0.0f ? rho : 1.0f;
-        rho = rho < kRhoMin ? kRhoMin : rho;
-
-        // ---- alpha: largest binary32 whose last level is <= rho
-        float alpha = 1.0f, inv_l2a = 0.0f, rdv = 0.0f, bias = 1.0f;
-        {
-            const bool need = rho < 1.0f;
-            const uint32_t ab = search_base<BV, G>(rho, need, lane, lig, gshift);
-            if (need) {
-                alpha = u2f(ab);
-                inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(alpha));
-                rdv = __builtin_amdgcn_rcpf(dv);
-                bias = 0.0f;
-            }
-        }
-
-        // ---- xi: one hashed start and stride per 8 elements; 1.5 + xi - 2^-24 as a float in [1,2)
-        const uint64_t gidx = (a.index_offset + e0) >> 3;
-        uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
-        uint32_t Y = mix32(X ^ a.key1) | 1u;
-        if (!a.stochastic) { X = 0x80000000u; Y = 0u; }     // xi = 0: the float is 1.5
-
-        // ---- encode: codes rounded in the float domain, four to an accumulator
-        // m: code - L = rint(m^ * L/Delta_m) in [-L, L];  v: code + 1 = floor(log_alpha(v^/Delta_v) + 1.5 + xi)
-        float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
-        uint32_t m8_de = 0;
-#pragma unroll
-        for (int j = 7; j >= 0; --j) {
-            float tm = 0.0f;
-            if (!MDE) {
-                tm = __builtin_rintf(mh[j] * inv_s);
-            } else {
-                // DE: nearest level on the magnitude; inv_s = 1/Delta_m.  j = #midpoints below |z|
-                const float z = mh[j] * inv_s;
-                const float az = __builtin_fabsf(z);
-                uint32_t code;
-                if (kDeTable) {
-                    // entry of the bucket of |z| (16 bytes per bucket: z >= 0, then z < 0)
-                    // (clamped on both sides: a non-finite input must not leave the table)
-                    const uint32_t bk = umin(umax(__builtin_amdgcn_ubfe(f2u(z), 21u, 10u), DeBuckets<BM>::kLo),
-                                             DeBuckets<BM>::kHi);
-                    const uint32_t addr = ((f2u(z) >> 28) & 8u) | ((bk << 4) + de_base);
-                    const u32x2_t e = *(lds_u32x2_t *)(uintptr_t)addr;
-                    code = e.y + (z > u2f(e.x) ? 1u : 0u);
-                } else {
-                    // few levels: the code is the number of rounding boundaries below z.  A value
-                    // on a boundary keeps the level of smaller magnitude: '>' on the positive side,
-                    // '>=' on the negative one (z = -0 is above every negative boundary: code L).
-                    (void)az;
-                    code = 0;
-#pragma unroll
-                    for (int k = 0; k < L; ++k) code += (z >= -DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
-#pragma unroll
-                    for (int k = 0; k <= L; ++k) code += (z > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
-                }
-                if (TAIL && !ok[j]) code = 0;
-                m8_de |= code << (BM * j);
-            }
-            const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, X + (uint32_t)j * Y, 9u));
-            const float ratio = __builtin_fmaf(vh[j], rdv, bias);
-            float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, f));
-            tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));   // +inf (v^ = 0) takes the last code
-            if (TAIL && !ok[j]) { tm = -(float)L; tv = 1.0f; }
-            if (j == 7)      { am_hi = tm; av_hi = tv; }
-            else if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
-            else if (j == 3) { am_lo = tm; av_lo = tv; }
-            else             { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
-        }
-        constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));   // L * sum 2^(BM j), j < 4
-        constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
-        const uint32_t m8 = MDE ? m8_de : ((uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM)));
-        const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
+        // ---- the block's encoder constants, then this lane's 8 codes of each moment
+        const BlockCodec codec = block_codec<BV, G, L, MDE>(xp_bits, dm, dv, lane, lig, gshift);
+        const float alpha = codec.alpha;
+        uint32_t m8, v8;
+        encode_run<BM, BV, MDE, TAIL>(a, e0, mh, vh, ok, codec, de_base, m8, v8);
 
         // ---- update the state image in place: XOR turns this lane's old fields into the new
         // ones and leaves the neighbours' fields of a shared word alone
@@ -1008,12 +1079,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     if (!TAIL) {
-        u32x4_t *gm = reinterpret_cast<u32x4_t *>(a.m_words + tile * MW);
-        u32x4_t *gv = reinterpret_cast<u32x4_t *>(a.v_words + tile * VW);
-        for (uint32_t q = lane; q < MW / 4; q += 64)
-            stream_store_u4(gm + q, *reinterpret_cast<const u32x4_t *>(img_m + 4 * q));
-        for (uint32_t q = lane; q < VW / 4; q += 64)
-            stream_store_u4(gv + q, *reinterpret_cast<const u32x4_t *>(img_v + 4 * q));
+        store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
     } else {
         for (uint32_t w = lane; w < MW; w += 64) {
             const uint64_t gw = tile * MW + w;
@@ -1023,13 +1089,13 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             const uint64_t gw = tile * VW + w;
             if (gw < v_total) a.v_words[gw] = img_v[w];
         }
-    }
-    for (uint32_t b = lane; b < NBT; b += 64) {
-        const uint64_t gb = tile * NBT + b;
-        if (!TAIL || gb < nblk) {
-            a.m_scale[gb] = sc[b];
-            a.v_scale[gb] = sc[NBT + b];
-            a.v_base[gb] = sc[2 * NBT + b];
+        for (uint32_t b = lane; b < NBT; b += 64) {
+            const uint64_t gb = tile * NBT + b;
+            if (gb < nblk) {
+                a.m_scale[gb] = sc[b];
+                a.v_scale[gb] = sc[NBT + b];
+                a.v_base[gb] = sc[2 * NBT + b];
+            }
         }
     }
 }
@@ -1102,7 +1168,6 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
     constexpr int VT = K + 1;
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
     constexpr int MTS = Lay::MTS;
-    constexpr uint32_t GMASK = (1u << G) - 1u;
     constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
     constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
     constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
@@ -1128,54 +1193,9 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
     float4 *const st2_c = stage + (lane + lane / 8u);       // + 72 k
     float4 *const st2_l = stage + (2u * lane + lane / 4u);  // + c
 
-    // ---- stage the super-tile's state in LDS: every load is issued before the first wait
-    static_assert(MW % 4 == 0 && VW % 4 == 0 && kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
-    {
-        constexpr int RM = (MW / 4 + 63) / 64, RV = (VW / 4 + 63) / 64, RS = (NBT + 63) / 64;
-        const u32x4_t *gm = reinterpret_cast<const u32x4_t *>(a.m_words + tile * MW);
-        const u32x4_t *gv = reinterpret_cast<const u32x4_t *>(a.v_words + tile * VW);
-        u32x4_t xm[RM], xv[RV];
-        float s_dm[RS], s_dv[RS], s_al[RS];
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < MW / 4) xm[r] = __builtin_nontemporal_load(gm + q);
-        }
-#pragma unroll
-        for (int r = 0; r < RV; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < VW / 4) xv[r] = __builtin_nontemporal_load(gv + q);
-        }
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            const uint32_t bb = lane + 64u * r;
-            if (bb < NBT) {
-                const uint64_t gb = tile * NBT + bb;
-                s_dm[r] = a.m_scale[gb]; s_dv[r] = a.v_scale[gb]; s_al[r] = a.v_base[gb];
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < MW / 4) {
-                if (BM == 3) xm[r] &= 0x3FFFFFFFu;
-                *reinterpret_cast<u32x4_t *>(img_m + 4 * q) = xm[r];
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < RV; ++r) {
-            const uint32_t q = lane + 64u * r;
-            if (q < VW / 4) {
-                if (BV == 3) xv[r] &= 0x3FFFFFFFu;
-                *reinterpret_cast<u32x4_t *>(img_v + 4 * q) = xv[r];
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            const uint32_t bb = lane + 64u * r;
-            if (bb < NBT) { sc[bb] = s_dm[r]; sc[NBT + bb] = s_dv[r]; sc[2 * NBT + bb] = s_al[r]; }
-        }
-    }
+    // ---- stage the super-tile's state in LDS
+    static_assert(kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
+    load_state_image<BM, BV, MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
     if (lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1209,8 +1229,8 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const uint32_t e = e_loc + 8u * r;
-            wm[r] = (CM == 10) ? (e * 52429u) >> 19 : e / CM; sm[r] = e - wm[r] * CM;
-            wv[r] = (CV == 10) ? (e * 52429u) >> 19 : e / CV; sv[r] = e - wv[r] * CV;
+            wm[r] = (CM == 10) ? __umul24(e, 52429u) >> 19 : e / CM; sm[r] = e - wm[r] * CM;
+            wv[r] = (CV == 10) ? __umul24(e, 52429u) >> 19 : e / CV; sv[r] = e - wv[r] * CV;
         }
 
         // ---- old state of the block and of this lane's elements (LDS)
@@ -1351,105 +1371,19 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
             col[16] = kInfBits;
 #pragma unroll
             for (int c = 0; c < 8; ++c) *reinterpret_cast<uint2 *>(col + 2 * c) = make_uint2(key[2 * c], key[2 * c + 1]);
-            uint32_t head = key[0], behind = key[1], haddr = col_addr;
-            for (uint32_t k = 0; k < a.rank_full; ++k) {
-                const uint32_t mn = group_reduce<G>(head, UMin());
-                uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
-                if (__builtin_expect(__builtin_popcountll(holders) != NG, 0)) {
-                    uint64_t lowest = 0;           // a tie: the lowest holder of each group pops
-#pragma unroll
-                    for (int gi = 0; gi < NG; ++gi) {
-                        const uint64_t f = (holders >> (gi * G)) & (uint64_t)GMASK;
-                        lowest |= (f & (0 - f)) << (gi * G);
-                    }
-                    holders = lowest;
-                }
-                xp_bits = mn;
-                uint64_t saved;
-                asm volatile("s_mov_b64 %[saved], exec\n\t"
-                             "s_mov_b64 exec, %[holders]\n\t"
-                             "s_waitcnt lgkmcnt(0)\n\t"
-                             "v_mov_b32_e32 %[head], %[behind]\n\t"
-                             "ds_read_b32 %[behind], %[haddr] offset:8\n\t"
-                             "v_add_u32_e32 %[haddr], 4, %[haddr]\n\t"
-                             "s_mov_b64 exec, %[saved]"
-                             : [head] "+v"(head), [behind] "+v"(behind), [haddr] "+v"(haddr), [saved] "=&s"(saved)
-                             : [holders] "s"(holders)
-                             : "memory");
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(behind) : : "memory");
+            xp_bits = extract_rth<G>(key[0], key[1], col_addr, a.rank_full);
         }
 
-        // ---- rho = x_p / Delta_v (even lanes) and L / Delta_m (odd lanes): one division
-        const float num = (lane & 1u) ? (MDE ? 1.0f : (float)L) : u2f(xp_bits);
-        const float den = (lane & 1u) ? dm : dv;
-        const float quo = num / den;
-        float rho = u2f(dpp<0xA0>(f2u(quo)));
-        float inv_s = u2f(dpp<0xF5>(f2u(quo)));
-        inv_s = dm > 0.0f ? inv_s : 0.0f;
-        rho = dv > 0.0f ? rho : 1.0f;
-        rho = rho < kRhoMin ? kRhoMin : rho;
-
-        // ---- alpha: largest binary32 whose last level is <= rho
-        float alpha = 1.0f, inv_l2a = 0.0f, rdv = 0.0f, bias = 1.0f;
-        {
-            const bool need = rho < 1.0f;
-            const uint32_t ab = search_base<BV, G>(rho, need, lane, lig, gshift);
-            if (need) {
-                alpha = u2f(ab);
-                inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(alpha));
-                rdv = __builtin_amdgcn_rcpf(dv);
-                bias = 0.0f;
-            }
-        }
+        // ---- the block's encoder constants
+        const BlockCodec codec = block_codec<BV, G, L, MDE>(xp_bits, dm, dv, lane, lig, gshift);
+        const float alpha = codec.alpha;
 
         // ---- encode and update the state image, one run of 8 elements at a time
         uint32_t m_word = 0, v_word = 0;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            const uint64_t gidx = (a.index_offset + e0 + 8u * r) >> 3;
-            uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
-            uint32_t Y = mix32(X ^ a.key1) | 1u;
-            if (!a.stochastic) { X = 0x80000000u; Y = 0u; }
-            float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
-            uint32_t m8_de = 0;
-#pragma unroll
-            for (int j = 7; j >= 0; --j) {
-                const float mhj = mh[8 * r + j], vhj = vh[8 * r + j];
-                float tm = 0.0f;
-                if (!MDE) {
-                    tm = __builtin_rintf(mhj * inv_s);
-                } else {
-                    const float z = mhj * inv_s;
-                    uint32_t code;
-                    if (kDeTable) {
-                        const uint32_t bk = umin(umax(__builtin_amdgcn_ubfe(f2u(z), 21u, 10u), DeBuckets<BM>::kLo),
-                                                 DeBuckets<BM>::kHi);
-                        const uint32_t addr = ((f2u(z) >> 28) & 8u) | ((bk << 4) + de_base);
-                        const u32x2_t e = *(lds_u32x2_t *)(uintptr_t)addr;
-                        code = e.y + (z > u2f(e.x) ? 1u : 0u);
-                    } else {
-                        code = 0;
-#pragma unroll
-                        for (int k = 0; k < L; ++k) code += (z >= -DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
-#pragma unroll
-                        for (int k = 0; k <= L; ++k) code += (z > DeLevels<BM>::tab.mid[k]) ? 1u : 0u;
-                    }
-                    m8_de |= code << (BM * j);
-                }
-                const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, X + (uint32_t)j * Y, 9u));
-                const float ratio = __builtin_fmaf(vhj, rdv, bias);
-                float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), inv_l2a, f));
-                tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));
-                if (j == 7)      { am_hi = tm; av_hi = tv; }
-                else if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
-                else if (j == 3) { am_lo = tm; av_lo = tv; }
-                else             { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
-            }
-            constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));
-            constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));
-            const uint32_t m8 = MDE ? m8_de : ((uint32_t)(am_lo + OFFM) | ((uint32_t)(am_hi + OFFM) << (4 * BM)));
-            const uint32_t v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
+            uint32_t m8, v8;
+            encode_run<BM, BV, MDE, false>(a, e0 + 8u * r, mh + 8 * r, vh + 8 * r, nullptr, codec, de_base, m8, v8);
             // 3-bit codes share words between lanes: XOR turns this lane's old fields into the new
             // ones and leaves the neighbours' alone.  2- and 4-bit words belong to one lane.
             if (BM == 3) {
@@ -1479,20 +1413,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
     // ---- write the super-tile's state back (coalesced)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    {
-        u32x4_t *gm = reinterpret_cast<u32x4_t *>(a.m_words + tile * MW);
-        u32x4_t *gv = reinterpret_cast<u32x4_t *>(a.v_words + tile * VW);
-        for (uint32_t q = lane; q < MW / 4; q += 64)
-            stream_store_u4(gm + q, *reinterpret_cast<const u32x4_t *>(img_m + 4 * q));
-        for (uint32_t q = lane; q < VW / 4; q += 64)
-            stream_store_u4(gv + q, *reinterpret_cast<const u32x4_t *>(img_v + 4 * q));
-    }
-    for (uint32_t b = lane; b < NBT; b += 64) {
-        const uint64_t gb = tile * NBT + b;
-        a.m_scale[gb] = sc[b];
-        a.v_scale[gb] = sc[NBT + b];
-        a.v_base[gb] = sc[2 * NBT + b];
-    }
+    store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
 }
 
 // The DE bucket table of a workgroup: copied from constant memory once, before any wavefront
