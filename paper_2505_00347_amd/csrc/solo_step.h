@@ -978,7 +978,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
             if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
             m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
-            v_max = __builtin_fmaxf(v_max, vh[j]);
+            if (TAIL) v_max = __builtin_fmaxf(v_max, vh[j]);     // (full tiles: the last sorted key below)
         }
         if (EXT && a.param_bf16) {                    // 16-bit copy of the new parameters, 16 bytes per lane
             if (!TAIL) {
@@ -1004,17 +1004,17 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
         }
 
-        // ---- block maxima (non-negative floats order like their bit patterns)
-        float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
-        float dv = u2f(group_reduce<G>(f2u(v_max), UMax()));
-        if (dm < kTiny) dm = 0.0f;
-        if (dv < kTiny) dv = 0.0f;
-
-        // ---- the r-th smallest v^ of the block
+        // ---- the lane's v^ sorted (non-negative floats order like their bit patterns); block maxima
         uint32_t key[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) key[j] = (TAIL && !ok[j]) ? kInfBits : f2u(vh[j]);
         sort8(key);
+        float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
+        float dv = u2f(group_reduce<G>(TAIL ? f2u(v_max) : key[7], UMax()));
+        if (dm < kTiny) dm = 0.0f;
+        if (dv < kTiny) dv = 0.0f;
+
+        // ---- the r-th smallest v^ of the block
         col[8] = kInfBits;                      // sentinel behind the lane's 8 keys (the staging overwrote it)
         *reinterpret_cast<uint4 *>(col) = make_uint4(key[0], key[1], key[2], key[3]);
         *reinterpret_cast<uint4 *>(col + 4) = make_uint4(key[4], key[5], key[6], key[7]);
@@ -1309,7 +1309,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
 
         // ---- dequantize (table look-up), EMA, parameter
         float mh[16], vh[16];
-        float m_absmax = 0.0f, v_max = 0.0f;
+        float m_absmax = 0.0f;
         const float kb = a.belief ? 1.0f : 0.0f;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -1328,7 +1328,6 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
             const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
             p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
             m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
-            v_max = __builtin_fmaxf(v_max, vh[j]);
         }
         // ---- new parameters back to the coalesced layout, streamed out
         wave_lds_sync();
@@ -1355,19 +1354,19 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         }
         wave_lds_sync();                        // the staging area becomes the column area
 
-        // ---- block maxima
+        // ---- the lane's v^ sorted (non-negative floats order like their bit patterns), the block
+        // maxima (the lane's largest v^ is its last key), the r-th smallest v^ of the block
         float dm = u2f(group_reduce<G>(f2u(m_absmax), UMax()));
-        float dv = u2f(group_reduce<G>(f2u(v_max), UMax()));
         if (dm < kTiny) dm = 0.0f;
-        if (dv < kTiny) dv = 0.0f;
-
-        // ---- the r-th smallest v^ of the block
+        float dv;
         uint32_t xp_bits = 0;
         {
             uint32_t key[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j) key[j] = f2u(vh[j]);
             sort16(key);
+            dv = u2f(group_reduce<G>(key[15], UMax()));
+            if (dv < kTiny) dv = 0.0f;
             col[16] = kInfBits;
 #pragma unroll
             for (int c = 0; c < 8; ++c) *reinterpret_cast<uint2 *>(col + 2 * c) = make_uint2(key[2 * c], key[2 * c + 1]);
