@@ -856,10 +856,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     float *const my_tm = reinterpret_cast<float *>(slab + kOffTm) + grp * MTS;
     const uint32_t tv_addr = lds_addr(my_tv), tm_addr = lds_addr(my_tm);   // aligned to the table size
     const uint32_t col_addr = lds_addr(col);
-    // word and slot of this lane's first code in iteration 0; an iteration advances both
-    // streams by 512 codes = (512 / C) words and (512 % C) slots
-    uint32_t wm = (lane * 8u) / CM, sm = (lane * 8u) % CM;
-    uint32_t wv = (lane * 8u) / CV, sv = (lane * 8u) % CV;
 
     // DE codebook: the levels of the table entries this lane fills (entries lig, lig + G)
     float de_level[(16 + G - 1) / G];
@@ -875,6 +871,11 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         const uint32_t e_loc = (uint32_t)it * kIter + lane * 8u;   // element inside the tile
         const uint64_t e0 = tile_e0 + e_loc;
         const uint32_t bl = (uint32_t)it * NG + grp;               // block inside the tile
+        // word and slot of this lane's first code (recomputed in every iteration: cheaper in
+        // registers than carrying them; e / 10 by multiplication, exact far beyond the tile size)
+        static_assert(kTile <= 20480, "range of the division by 10");
+        const uint32_t wm = (CM == 10) ? __umul24(e_loc, 52429u) >> 19 : e_loc / CM, sm = e_loc - wm * CM;
+        const uint32_t wv = (CV == 10) ? __umul24(e_loc, 52429u) >> 19 : e_loc / CV, sv = e_loc - wv * CV;
         // elements of this lane's block that exist (B except in the last block)
         uint32_t nb = B;
         bool blk_ok = true;
@@ -1068,11 +1069,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         }
         if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
         (void)blk_ok;
-
-        wm += kIter / CM; sm += kIter % CM;
-        if (sm >= (uint32_t)CM) { sm -= CM; wm += 1; }
-        wv += kIter / CV; sv += kIter % CV;
-        if (sv >= (uint32_t)CV) { sv -= CV; wv += 1; }
     }
 
     // ---- write the super-tile's state back (coalesced)
