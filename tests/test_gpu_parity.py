@@ -486,6 +486,7 @@ def test_step_can_be_captured_in_a_hip_graph(so, gpu):
                                                              (2, 3, 128, True, False, "adamw", True),
                                                              (4, 2, 128, True, True, "adamw", True),
                                                              (3, 3, 64, False, False, "adabelief", True),
+                                                             (2, 2, 64, False, True, "adamw", True),
                                                              (4, 4, 128, False, False, "adam_l2", False)])
 def test_multi_tensor_step_equals_per_tensor_steps(so, gpu, bm, bv, B, bf16, de, optimizer, extras):
     """solo_adamw_step_multi over tensors of awkward sizes (empty, smaller than a block, one
