@@ -5,7 +5,14 @@ Both sides receive the same seeded inputs.  The bar, per step:
   * 1st-moment code words: bit-exact;
   * 2nd-moment codes: equal, except +-1 flips where the oracle's own binary64
     margin to the rounding boundary is below FLIP_MARGIN (the two sides use
-    different log2 routines); at most 1e-5 of the elements;
+    different log2 routines); at most 1e-5 of the elements.  In a block whose
+    base alpha lies within a few thousand ulps of 1 (a nearly constant block)
+    log_alpha amplifies the last bit of v^/Delta itself: one unit in the last
+    place of the ratio moves the rounded quantity by 2^-23 / |ln alpha| code
+    units, and the two sides form the ratio differently (a division on the CPU,
+    a reciprocal and a product on the GPU, up to two units apart).  There the
+    margin a flip may have grows by 4 * 2^-23 / |log2 alpha| (flip_allowance),
+    and such flips are not counted against the 1e-5 rate;
   * parameters: |dp| <= 1e-6 |p| + 2e-6 lr after one step from equal states, and
     <= 1e-5 |p| + 1e-5 lr after ten free-running steps (a parameter can be
     arbitrarily close to zero while every step moves it by O(lr); the kernel's
@@ -20,6 +27,13 @@ pytestmark = pytest.mark.gpu
 TILE = 5120          # elements one wavefront of the step kernel owns (sizes below span several)
 FLIP_MARGIN = 5e-5
 FLIP_RATE = 1e-5
+
+
+def flip_allowance(alpha):
+    """Largest oracle margin (code units) at which a +-1 disagreement of a 2nd-moment code is
+    legitimate, per element, from the element's block base."""
+    l2a = np.abs(np.log2(np.minimum(alpha.astype(np.float64), 1.0 - 2.0 ** -25)))
+    return FLIP_MARGIN + 4.0 * 2.0 ** -23 / l2a
 
 
 @pytest.fixture(scope="module")
@@ -120,11 +134,21 @@ def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainte
     if tainted is None:
         assert np.array_equal(gm, want_st.m_words), "1st-moment words differ (pad bits?)"
     diff = np.nonzero((hv != wv) & eclean)[0]
+    n_flips = 0
     if diff.size:
         d = np.abs(hv[diff].astype(int) - wv[diff].astype(int))
         assert d.max() == 1, f"2nd-moment code off by {d.max()} at {diff[np.argmax(d)]}"
-        assert margin[diff].max() < FLIP_MARGIN, \
-            f"2nd-moment flip away from a tie: margin {margin[diff].max():.3g} at {diff[np.argmax(margin[diff])]}"
+        allow = flip_allowance(np.repeat(want_st.v_base, B)[:n])
+        over = margin[diff] - allow[diff]
+        assert over.max() < 0, \
+            f"2nd-moment flip away from a tie: margin {margin[diff][np.argmax(over)]:.3g} at {diff[np.argmax(over)]}"
+        # blocks in which the allowance is essentially FLIP_MARGIN count against the flip rate;
+        # in the others a flip has probability ~2 x allowance per element, which bounds their number
+        well = allow[diff] < 2 * FLIP_MARGIN
+        n_flips = int(well.sum())
+        ill_elems = allow[eclean] >= 2 * FLIP_MARGIN
+        assert int((~well).sum()) <= 10 + 4 * float(allow[eclean][ill_elems].clip(max=0.5).sum()), \
+            "too many flips in nearly constant blocks"
         if tainted is not None:
             tainted[np.unique(diff // B)] = True
     elif tainted is None:
@@ -133,7 +157,7 @@ def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainte
     tol = p_rtol * np.abs(want_p) + p_atol
     bad = (err > tol) & eclean
     assert not bad.any(), f"parameter error {err[bad].max():.3g} at {np.nonzero(bad)[0][0]}"
-    return diff.size
+    return n_flips
 
 
 def grads_for(kind, n, std, seed, bf16):
@@ -364,6 +388,18 @@ def special_grads(n, B, seed):
     g[5 * B:6 * B] = 1e-18                     # underflows to the zero block
     g[6 * B:7 * B:2] = 0                       # half zeros
     return g
+
+
+@pytest.mark.parametrize("eps", (1e-12, 1e-13))
+def test_nearly_constant_blocks(so, gpu, eps):
+    """AdaBelief whose eps dwarfs the squared residuals (gradients of 5e-8 after the scale): every
+    v^ of a block lies within 1e-5 of eps, the base alpha within a few dozen ulps of 1, and the
+    code of an element hangs on the last bit of v^/Delta.  Scales and bases still agree bit for
+    bit, codes differ by at most one, and only within the margin flip_allowance grants."""
+    kw = dict(de=True, optimizer="adabelief", p=0.02, eps=eps, grad_scale=1.0 / 1024, seed=146131703902,
+              off=265625140904, kind="student_t3", std=5.4e-5)
+    run_teacher_forced(so, gpu, 13899, 2, 3, 128, bf16=True, steps=3, seed0=358133, **kw)
+    run_teacher_forced(so, gpu, 3 * TILE + 100, 4, 4, 64, bf16=False, steps=2, seed0=11, **kw)
 
 
 @pytest.mark.parametrize("bm,bv,B,bf16,de", [(2, 3, 128, False, False), (4, 4, 64, False, False),
