@@ -13,7 +13,7 @@ Both sides receive the same seeded inputs.  The bar, per step:
     a reciprocal and a product on the GPU, up to two units apart).  There the
     margin a flip may have grows by 4 * 2^-23 / |log2 alpha| (flip_allowance),
     and such flips are not counted against the 1e-5 rate;
-  * parameters: |dp| <= 1e-6 |p| + 2e-6 lr after one step from equal states, and
+  * parameters: |dp| <= 1e-6 |p| + 2e-6 lr + 4e-7 |update| after one step from equal states, and
     <= 1e-5 |p| + 1e-5 lr after ten free-running steps (a parameter can be
     arbitrarily close to zero while every step moves it by O(lr); the kernel's
     sqrt and reciprocal are good to 1 ulp, so one step is off by ~1e-7 of its
@@ -27,6 +27,13 @@ pytestmark = pytest.mark.gpu
 TILE = 5120          # elements one wavefront of the step kernel owns (sizes below span several)
 FLIP_MARGIN = 5e-5
 FLIP_RATE = 1e-5
+
+
+def flip_budget(codes):
+    """Flips tolerated among `codes` compared codes: the 1e-5 rate as a mean, with room for its
+    Poisson scatter (every single flip has already been checked against its margin)."""
+    mean = FLIP_RATE * codes
+    return mean + 4.0 * np.sqrt(mean) + 2.0
 
 
 def flip_allowance(alpha):
@@ -117,7 +124,7 @@ def bits_equal(a, b):
     return np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
-def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainted=None):
+def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainted=None, p_before=None):
     """Compare one step's results; returns the number of v-code flips.  `tainted` (bool per
     block, updated in place) marks blocks whose state already differs legitimately."""
     B = oc.block_size
@@ -155,6 +162,11 @@ def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainte
         assert np.array_equal(gv, want_st.v_words), "2nd-moment words differ (pad bits?)"
     err = np.abs(gp.astype(np.float64) - want_p)
     tol = p_rtol * np.abs(want_p) + p_atol
+    if p_before is not None:
+        # the binary32 update (hardware sqrt and reciprocal, 1 ulp each) is off by a few 1e-7 of its
+        # own size; p_atol covers that for updates of O(10 lr), this term for the settings in which
+        # an update is orders of magnitude larger (a vanishing v^ under an eps of 1e-12, say)
+        tol = tol + 4e-7 * np.abs(want_p.astype(np.float64) - p_before)
     bad = (err > tol) & eclean
     assert not bad.any(), f"parameter error {err[bad].max():.3g} at {np.nonzero(bad)[0][0]}"
     return n_flips
@@ -181,10 +193,11 @@ def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal
         g, g_dev = grads_for(kind, n, std, seed0 + step, bf16)
         side.load(p, st)
         side.step(g_dev, step)
+        p_before = p.astype(np.float64)
         margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
-        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
+        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr, p_before=p_before)
         side.check_bf16_copy(so)
-    assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
+    assert flips <= flip_budget(n * steps), f"{flips} flips in {n * steps} codes"
     return flips
 
 
@@ -213,7 +226,7 @@ def run_free(so, solo, n, bm, bv, B, bf16=False, steps=10, kind="normal", std=1e
             # the two parameter updates would leak into the states, so the oracle continues from
             # the kernel's parameters (the states stay free-running)
             p[:] = got[0]
-    assert flips <= max(2, FLIP_RATE * n * steps), f"{flips} flips in {n * steps} codes"
+    assert flips <= flip_budget(n * steps), f"{flips} flips in {n * steps} codes"
     assert tainted.mean() <= max(2.0 / tainted.size, 2 * FLIP_RATE * B * steps)
     return flips, int(tainted.sum())
 
