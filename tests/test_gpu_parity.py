@@ -610,6 +610,40 @@ def test_multi_tensor_table_rejects_bad_descriptors(gpu):
     assert solo.solo_adamw_step_multi(p.data_ptr(), 1, 2, 0, None, 0, cfg, check=False) == solo.SOLO_E_INVALID
 
 
+# ------------------------------------------------------------------- randomized sweep
+
+@pytest.mark.parametrize("seed", (1, 2, 3))
+def test_randomized_sweep(so, gpu, seed):
+    """Forty seeded random combinations per seed of format, block size, codebook, gradient type and
+    distribution, optimizer, quantile, size (ragged ends included), hyper-parameters, xi on/off,
+    stream position and extras, with gradient magnitudes from 1e-15 to 1e6: three steps each from
+    equal states.  (Sweeps of this kind are what found the nearly-constant-block regime.)"""
+    rng = np.random.default_rng(seed)
+    for c in range(40):
+        bm, bv = int(rng.integers(2, 5)), int(rng.integers(2, 5))
+        B = int(rng.choice([64, 128]))
+        de, bf16 = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        opt = str(rng.choice(["adamw", "adamw", "adam_l2", "adabelief"]))
+        n = int(rng.choice([rng.integers(1, 3000), rng.integers(3000, 40000),
+                            TILE * int(rng.integers(1, 6)) + int(rng.integers(0, TILE))]))
+        kind = str(rng.choice(["normal", "student_t3", "normal_outliers"]))
+        std = float(10.0 ** rng.uniform(-15, 6)) if rng.integers(0, 3) == 0 else float(10.0 ** rng.uniform(-6, 0))
+        kw = dict(de=de, optimizer=opt, p=float(rng.choice([0.0, 0.02, 0.1, 0.1, 0.25, 0.6, 0.95])),
+                  stochastic=int(rng.integers(0, 4) > 0), seed=int(rng.integers(0, 2 ** 40)),
+                  off=8 * int(rng.integers(0, 2 ** 36)), eps=1e-12 if opt == "adabelief" else 1e-8)
+        if rng.integers(0, 2):
+            kw.update(beta1=float(rng.choice([0.0, 0.1, 0.5, 0.9, 0.95])),
+                      beta2=float(rng.choice([0.0, 0.9, 0.98, 0.999, 0.9999])),
+                      lr=float(rng.choice([0.0, 1e-5, 1e-3, 1e-1])), wd=float(rng.choice([0.0, 0.01, 0.5])))
+        if rng.integers(0, 2):
+            kw.update(grad_scale=float(rng.choice([1.0, 0.5, 1.0 / 1024])), bf16_copy=True)
+        try:
+            run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, kind=kind, std=std,
+                               seed0=int(rng.integers(0, 10 ** 6)), **kw)
+        except AssertionError as e:
+            raise AssertionError(f"case {c}: n={n} m{bm} v{bv} B{B} bf16={bf16} {kind} std={std:.3g} {kw}: {e}") from e
+
+
 # ---------------------------------- the benchmark's workload at its full size, sampled
 
 @pytest.mark.parametrize("name,variant", [("c5_llama7b_2bit_3bit", "plain"), ("paper_4_2bit_llama7b", "mp")])
