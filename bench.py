@@ -286,7 +286,10 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name) if (args.variant, args.launch) == ("adamw", "flat") else None,
                      "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3,
                      "stream_probe": probe},
-        "placement": {"candidates_ms": trial_ms, "chosen": chosen},
+        # (frac_first: what the roofline fraction would be on the first allocation as it came,
+        # from its warm-up steps)
+        "placement": {"candidates_ms": trial_ms, "chosen": chosen,
+                      "frac_first": (bpp * n / (trial_ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBS) if trial_ms[0] else None},
     }
     del res, p
     torch.cuda.empty_cache()
