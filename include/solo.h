@@ -126,7 +126,10 @@ int solo_state_init(uint32_t *m_codes, float *m_scale,
  * Gradients must be finite and so must their squares in binary32 (|g| < 1.8e19);
  * the result for other inputs is unspecified (no call hangs or faults: every loop
  * of the kernels is bounded and every table index is clamped).  A block whose new
- * maximum is below 2^-100 is stored as a zero block. */
+ * maximum is below 2^-100 is stored as a zero block.
+ * Performance note: on MI355X the step time of a large buffer depends by up to 10 % on
+ * where the buffers (the two code buffers above all) lie in physical memory; a long-lived
+ * optimizer can allocate its state a few times and keep the allocation that steps fastest. */
 int solo_adamw_step(float *param, const void *grad,
                     uint32_t *m_codes, float *m_scale,
                     uint32_t *v_codes, float *v_scale, float *v_base,
