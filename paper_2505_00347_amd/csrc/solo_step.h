@@ -62,7 +62,6 @@ constexpr int kLdsPerCu = 160 * 1024;
 #define SOLO_WAVES 4
 #endif
 constexpr int kWaves = SOLO_WAVES; // wavefronts per workgroup
-static_assert(kWaves >= 2, "the ragged end of a flat buffer is launched as up to two wavefronts of one workgroup");
 constexpr int kXcds = 8;           // accelerator dies of an MI355X (each has its own L2)
 constexpr int kColStride = 12;     // words per lane in the sorted-column area (8 keys, +inf, pad)
 constexpr int kIter16 = 1024;      // elements per iteration of the wide path (64 lanes x 16)
@@ -83,7 +82,8 @@ struct StepArgs {
     float *v_base;
     uint64_t n;             // elements
     uint64_t n_tiles_full;  // super-tiles that lie entirely inside [0, n)
-    uint64_t tail_tile0;    // first 2560-element unit behind them (the ragged end: one wavefront per unit)
+    uint64_t tail_tile0;    // first 2560-element unit behind them (the ragged end)
+    uint64_t tail_chunks;   // 512-element iterations of the ragged end, one wavefront each
     uint64_t wg_per_xcd;    // workgroups per XCD: ceil(ceil(n_tiles_full / kWaves) / 8)
     uint64_t index_offset;  // global index of element 0 (multiple of 8)
     float beta1, omb1, beta2, omb2;
@@ -777,12 +777,16 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
 // AdaBelief, bf16 weight copy); the plain AdamW step runs the one without them.
 template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT, int TILE>
 __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile, const uint32_t lane,
-                                          uint32_t *const slab, const uint32_t *const lds_de)
+                                          uint32_t *const slab, const uint32_t *const lds_de, const int chunk = -1)
 {
+    // chunk >= 0 (TAIL only): this wavefront runs iteration `chunk` of the tile alone, next to
+    // other wavefronts that run the other iterations.  It stages the tile's state for reading and
+    // applies its code changes to the global words directly (atomic XOR: the fields that
+    // different wavefronts own in a shared word are disjoint) instead of writing the tile back.
+    const bool alone = TAIL && chunk >= 0;
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
     constexpr int kTile = TILE;
-    constexpr int kIters = kTile / kIter;
     using Lay = SlabLayout<BM, BV, B, MDE, kTile>;
     constexpr int NBT = kTile / B;                 // blocks per super-tile
     constexpr int L = (1 << (BM - 1)) - 1;
@@ -810,7 +814,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     uint32_t *const col = slab + kOffCol + lane * kColStride;
 
     // first parameters and gradients: in flight while the state image is staged
-    RawPG raw = load_pg<BF16, TAIL>(a, tile_e0, lane);
+    const int it_begin = alone ? chunk : 0, it_end = alone ? chunk + 1 : TILE / kIter;
+    RawPG raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)it_begin * kIter, lane);
     const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;      // uniform: the gradient is transformed first
     // one pad vector after every 8 keeps both the coalesced (index = lane) and the per-lane
     // (index = 2 lane, 2 lane + 1) accesses of the transposition free of bank conflicts
@@ -867,7 +872,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     }
 
 #pragma unroll 1
-    for (int it = 0; it < kIters; ++it) {
+    for (int it = it_begin; it < it_end; ++it) {
         const uint32_t e_loc = (uint32_t)it * kIter + lane * 8u;   // element inside the tile
         const uint64_t e0 = tile_e0 + e_loc;
         const uint32_t bl = (uint32_t)it * NG + grp;               // block inside the tile
@@ -950,7 +955,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
             for (int j = 0; j < 8; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
         }
         // next iteration's parameters and gradients, a whole iteration ahead of their use
-        if (it + 1 < kIters) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
+        if (it + 1 < it_end) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
         float mt[8], vt[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {       // byte offset 4 * code, OR-ed into the aligned table base
@@ -1055,19 +1060,27 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         // ---- update the state image in place: XOR turns this lane's old fields into the new
         // ones and leaves the neighbours' fields of a shared word alone
         const uint32_t xm = mc8 ^ m8, xv = vc8 ^ v8;
-        if (BM == 3) {
-            atomicXor(&img_m[wm], (xm << (3u * sm)) & 0x3FFFFFFFu);
-            atomicXor(&img_m[wm + 1], (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30));
+        const uint32_t xm0 = (BM == 3) ? (xm << (3u * sm)) & 0x3FFFFFFFu : xm << (BM * sm);
+        const uint32_t xm1 = (BM == 3) ? (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30) : 0u;
+        const uint32_t xv0 = (BV == 3) ? (xv << (3u * sv)) & 0x3FFFFFFFu : xv << (BV * sv);
+        const uint32_t xv1 = (BV == 3) ? (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30) : 0u;
+        if (TAIL && alone) {
+            const uint64_t gm = tile * MW + wm, gv = tile * VW + wv;
+            if (xm0 != 0u && gm < m_total) atomicXor(&a.m_words[gm], xm0);
+            if (BM == 3 && xm1 != 0u && gm + 1 < m_total) atomicXor(&a.m_words[gm + 1], xm1);
+            if (xv0 != 0u && gv < v_total) atomicXor(&a.v_words[gv], xv0);
+            if (BV == 3 && xv1 != 0u && gv + 1 < v_total) atomicXor(&a.v_words[gv + 1], xv1);
+            if (lig == 0 && blk_ok) {
+                const uint64_t gb = tile * NBT + bl;
+                a.m_scale[gb] = dm; a.v_scale[gb] = dv; a.v_base[gb] = alpha;
+            }
         } else {
-            atomicXor(&img_m[wm], xm << (BM * sm));
+            atomicXor(&img_m[wm], xm0);
+            if (BM == 3) atomicXor(&img_m[wm + 1], xm1);
+            atomicXor(&img_v[wv], xv0);
+            if (BV == 3) atomicXor(&img_v[wv + 1], xv1);
+            if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
         }
-        if (BV == 3) {
-            atomicXor(&img_v[wv], (xv << (3u * sv)) & 0x3FFFFFFFu);
-            atomicXor(&img_v[wv + 1], (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30));
-        } else {
-            atomicXor(&img_v[wv], xv << (BV * sv));
-        }
-        if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
         (void)blk_ok;
     }
 
@@ -1076,7 +1089,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     __builtin_amdgcn_wave_barrier();
     if (!TAIL) {
         store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
-    } else {
+    } else if (!alone) {
         for (uint32_t w = lane; w < MW; w += 64) {
             const uint64_t gw = tile * MW + w;
             if (gw < m_total) a.m_words[gw] = img_m[w];
@@ -1424,7 +1437,9 @@ __device__ __forceinline__ void load_de_table(uint32_t *lds_de)
 }
 
 // The step over one flat buffer.  Full super-tiles: one workgroup per kWaves of them.  TAIL: the
-// ragged end, cut into 2560-element units, one wavefront each.
+// ragged end, cut into 2560-element units and these into their 512-element iterations, one
+// wavefront each (a short tensor is a latency problem: five iterations in sequence would take
+// five times as long).
 template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT>
 __global__ __launch_bounds__(kWaves * 64, (!TAIL && wide_path<BM, BV, B, MDE>()) ? kWideWaves : SOLO_MIN_WAVES)
 void step_kernel(const StepArgs a)
@@ -1444,12 +1459,21 @@ void step_kernel(const StepArgs a)
     // group of super-tiles of XCD x's contiguous eighth of the buffer, so the wavefronts that
     // run at the same time on one XCD stream through one narrow address window.
     const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
-    const uint64_t tile = TAIL ? a.tail_tile0 + wave : wg * kWaves + wave;
-    if (TAIL ? tile * kTile >= a.n : tile >= a.n_tiles_full) return;
+    if (TAIL) {
+        // the ragged end: one wavefront per 512-element iteration of its 2560-element units
+        constexpr int kChunks = kTileUnit / kIter;
+        const uint64_t c = (uint64_t)blockIdx.x * kWaves + wave;
+        if (c >= a.tail_chunks) return;
+        step_tile<BM, BV, B, BF16, MDE, true, EXT, kTileUnit>(a, a.tail_tile0 + c / kChunks, lane,
+                                                              lds_slab + wave * Lay::kSlab, lds_de, (int)(c % kChunks));
+        return;
+    }
+    const uint64_t tile = wg * kWaves + wave;
+    if (tile >= a.n_tiles_full) return;
     if constexpr (kWide)
         step_tile16<BM, BV, B, BF16, MDE, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
-    else
-        step_tile<BM, BV, B, BF16, MDE, TAIL, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
+    else if constexpr (!TAIL)
+        step_tile<BM, BV, B, BF16, MDE, false, EXT, kTile>(a, tile, lane, lds_slab + wave * Lay::kSlab, lds_de);
 }
 
 // The step over many tensors in one launch.  Every tensor is cut into units of the format's
@@ -1503,7 +1527,10 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
     args.wg_per_xcd = ((args.n_tiles_full + kWaves - 1) / kWaves + kXcds - 1) / kXcds;
     const bool has_tail = (args.n % kTile) != 0;
     args.tail_tile0 = args.n_tiles_full * (kTile / kTileUnit);
-    const uint32_t tail_waves = (uint32_t)((args.n - args.tail_tile0 * kTileUnit + kTileUnit - 1) / kTileUnit);
+    // its 512-element iterations, up to the end of the last code word (80 = lcm of 16, 10 and 8
+    // codes per word): the unused fields of that word are written as zeros like every other field
+    const uint64_t tail_e0 = args.tail_tile0 * kTileUnit;
+    args.tail_chunks = ((args.n + 79) / 80 * 80 - tail_e0 + kIter - 1) / kIter;
     const bool ext = args.param_bf16 || args.grad_scale || args.belief || args.l2 != 0.0f;
     if (args.n_tiles_full) {
         const uint64_t grid = args.wg_per_xcd * kXcds;
@@ -1514,8 +1541,9 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (has_tail) {                            // the ragged end: one wavefront per 2560-element unit, always the full-featured kernel
-        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true, true>), dim3(1), dim3(64 * tail_waves), 0, stream, args);
+    if (has_tail) {                            // the ragged end: one wavefront per 512 elements, always the full-featured kernel
+        const uint32_t tail_groups = (uint32_t)((args.tail_chunks + kWaves - 1) / kWaves);
+        hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true, true>), dim3(tail_groups), dim3(kWaves * 64), 0, stream, args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
