@@ -1523,9 +1523,12 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
 {
     StepArgs args = args_in;                   // the tiling belongs to the instantiation
     constexpr int kTile = tile_elems<BM, BV, B, MDE>();
-    args.n_tiles_full = args.n / kTile;
+    // A short tensor is all latency: up to four units (a norm or bias vector) go to the kernel of
+    // the ragged end as a whole, one wavefront per 512 elements, instead of one per super-tile.
+    const bool small = args.n <= 4 * (uint64_t)kTileUnit;
+    args.n_tiles_full = small ? 0 : args.n / kTile;
     args.wg_per_xcd = ((args.n_tiles_full + kWaves - 1) / kWaves + kXcds - 1) / kXcds;
-    const bool has_tail = (args.n % kTile) != 0;
+    const bool has_tail = small ? args.n != 0 : (args.n % kTile) != 0;
     args.tail_tile0 = args.n_tiles_full * (kTile / kTileUnit);
     // its 512-element iterations, up to the end of the last code word (80 = lcm of 16, 10 and 8
     // codes per word): the unused fields of that word are written as zeros like every other field
