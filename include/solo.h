@@ -185,8 +185,10 @@ typedef struct solo_tensor {
     uint64_t n;            /* elements                                       */
 } solo_tensor;
 
-/* Number of units the tensors are cut into for cfg's state format (a unit is the 2560 or 5120
- * elements one wavefront of that format's kernel owns); 0 if cfg is invalid. */
+/* Number of work units the tensors are cut into for cfg's state format (a unit is the 2560 or
+ * 5120 elements one wavefront of that format's kernel owns; the ragged end of a tensor counts
+ * one unit per 512 elements, each a wavefront of its own); 0 if cfg is invalid.  At most 2^24
+ * tensors per table. */
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg);
 
 /* Bytes of the table for `count` tensors and `units` units. */

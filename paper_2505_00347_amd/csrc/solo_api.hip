@@ -252,7 +252,7 @@ uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo
     const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
                                                      (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
     uint64_t units = 0;
-    for (uint32_t k = 0; k < count; ++k) units += (tensors[k].n + unit - 1) / unit;
+    for (uint32_t k = 0; k < count; ++k) units += solo::multi_full_units(tensors[k].n, unit) + solo::multi_ragged_chunks(tensors[k].n, unit);
     return units;
 }
 
@@ -265,6 +265,7 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
                            void *table_host, size_t table_bytes, uint32_t *table_flags)
 {
     if (!solo::config_ok(cfg) || !tensors || !table_host || !table_flags || count == 0) return SOLO_E_INVALID;
+    if (count > solo::kMapTensorMask) return SOLO_E_UNSUPPORTED;      // the map keeps the tensor index in 24 bits
     const uint64_t units = solo_multi_units(tensors, count, cfg);
     if (table_bytes < solo_multi_table_bytes(count, units)) return SOLO_E_INVALID;
     if (units > (1ull << 31)) return SOLO_E_UNSUPPORTED;
@@ -290,9 +291,11 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
         e.n = t.n; e.unit0 = unit0;
         e.index_offset = xi_offset;
         e.reserved = 0;
-        const uint64_t nu = (t.n + unit - 1) / unit;
-        for (uint64_t u = 0; u < nu; ++u) map[unit0 + u] = k;
-        unit0 += nu;
+        // full units first, then the 512-element iterations of the ragged end, one entry each
+        const uint64_t nf = solo::multi_full_units(t.n, unit), nc = solo::multi_ragged_chunks(t.n, unit);
+        for (uint64_t u = 0; u < nf; ++u) map[unit0 + u] = k;
+        for (uint64_t c = 0; c < nc; ++c) map[unit0 + nf + c] = k | ((uint32_t)c << solo::kMapChunkShift) | solo::kMapRagged;
+        unit0 += nf + nc;
         xi_offset += (t.n + solo::kTileUnit - 1) / solo::kTileUnit * (uint64_t)solo::kTileUnit;
     }
     *table_flags = flags;

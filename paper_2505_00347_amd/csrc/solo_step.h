@@ -120,6 +120,18 @@ struct TensorEntry {
 };
 static_assert(sizeof(TensorEntry) == 96, "table layout");
 
+// An entry of the unit map: the tensor's index; for the ragged end of a tensor, which is cut into
+// its 512-element iterations with one entry (one wavefront) each, also the iteration and a flag.
+constexpr uint32_t kMapTensorMask = 0x00FFFFFFu, kMapRagged = 0x80000000u;
+constexpr int kMapChunkShift = 24;
+inline uint64_t multi_full_units(uint64_t n, uint64_t unit) { return n / unit; }
+inline uint64_t multi_ragged_chunks(uint64_t n, uint64_t unit)
+{
+    // up to the end of the last code word (80 = lcm of 16, 10 and 8 codes per word), whose unused
+    // fields are written as zeros like every other field
+    return n % unit ? ((n + 79) / 80 * 80 - n / unit * unit + 511) / 512 : 0;
+}
+
 struct MultiArgs {
     StepArgs common;              // the scalars of the step; pointers, n and index_offset come from the table
     const TensorEntry *entries;
@@ -1477,9 +1489,10 @@ void step_kernel(const StepArgs a)
 }
 
 // The step over many tensors in one launch.  Every tensor is cut into units of the format's
-// super-tile size; one wavefront takes one unit, finds its tensor in the table (a scalar look-up) and runs the full-
-// tile code on a unit that lies inside the tensor and the bounds-checked code on a tensor's
-// ragged last unit.  Blocks never span tensors: each tensor is quantized on its own.
+// super-tile size and its ragged end into 512-element iterations; one wavefront takes one entry
+// of the map, finds its tensor in the table (a scalar look-up) and runs the full-tile code on a
+// unit or the bounds-checked code on one iteration of a ragged end.  Blocks never span tensors:
+// each tensor is quantized on its own.
 template <int BM, int BV, int B, bool BF16, bool MDE, bool EXT>
 __global__ __launch_bounds__(kWaves * 64, (wide_path<BM, BV, B, MDE>() ? kWideWaves : SOLO_MIN_WAVES))
 void multi_kernel(const MultiArgs ma)
@@ -1497,19 +1510,22 @@ void multi_kernel(const MultiArgs ma)
     const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * ma.groups_per_xcd + (blockIdx.x / kXcds);
     const uint64_t unit = wg * kWaves + wave;
     if (unit >= ma.total_units) return;
-    const TensorEntry &e = ma.entries[ma.unit_map[unit]];       // uniform: scalar loads
+    const uint32_t me = ma.unit_map[unit];                      // uniform: scalar loads
+    const TensorEntry &e = ma.entries[me & kMapTensorMask];
     StepArgs a = ma.common;
     a.param = e.param; a.param_bf16 = e.param_bf16; a.grad = e.grad;
     a.m_words = e.m_words; a.m_scale = e.m_scale;
     a.v_words = e.v_words; a.v_scale = e.v_scale; a.v_base = e.v_base;
     a.n = e.n; a.index_offset = e.index_offset;
-    const uint64_t tile = unit - e.unit0;
     uint32_t *const slab = lds_slab + wave * Lay::kSlab;
-    if ((tile + 1) * kUnit <= a.n) {
+    if (!(me & kMapRagged)) {
+        const uint64_t tile = unit - e.unit0;
         if constexpr (kWide) step_tile16<BM, BV, B, BF16, MDE, EXT, kUnit>(a, tile, lane, slab, lds_de);
         else step_tile<BM, BV, B, BF16, MDE, false, EXT, kUnit>(a, tile, lane, slab, lds_de);
-    } else
-        step_tile<BM, BV, B, BF16, MDE, true, true, kUnit>(a, tile, lane, slab, lds_de);
+    } else {
+        step_tile<BM, BV, B, BF16, MDE, true, true, kUnit>(a, a.n / kUnit, lane, slab, lds_de,
+                                                           (int)((me >> kMapChunkShift) & 0x7Fu));
+    }
 }
 
 // Host-side launcher of one instantiation family (fixed bits_m and 1st-moment codebook);

@@ -109,8 +109,8 @@ def test_error_strings_and_host_side_rejections(solo):
 
 def test_multi_tensor_table_layout(solo):
     """The table of solo_adamw_step_multi is built by host code alone: 96 bytes per tensor
-    (eight pointers, n, first unit, xi offset, a reserved word), then one 32-bit tensor index per
-    unit.  The pointers are made-up, suitably aligned addresses; nothing touches a GPU."""
+    (eight pointers, n, first unit, xi offset, a reserved word), then one 32-bit entry per unit: the
+    tensor's index, and for the 512-element pieces of a ragged end also the piece and a flag.  The pointers are made-up, suitably aligned addresses; nothing touches a GPU."""
     import numpy as np
     cfg = solo.make_config(2, 3, 128, 1, index_offset=8 * 77)
     sizes = [3000, 0, 5120, 12800 + 1, 64]
@@ -120,9 +120,11 @@ def test_multi_tensor_table_layout(solo):
         arr[k] = solo.solo_tensor(base, base + 0x1000000 if k == 2 else None, base + 0x2000000, base + 0x3000000,
                                   base + 0x4000000, base + 0x5000000, base + 0x6000000, base + 0x7000000, n)
     units = solo.solo_multi_units(arr, len(sizes), cfg)
-    unit = 5120 if units == 1 + 0 + 1 + 3 + 1 else 2560
-    per_tensor = [-(-n // unit) for n in sizes]
-    assert units == sum(per_tensor)
+    unit = 5120                       # the super-tile of this format; a ragged end counts one unit per 512
+    full = [n // unit for n in sizes]   # elements, up to the end of its last code word (a multiple of 80)
+    ragged = [-(-(-(-n // 80) * 80 - n // unit * unit) // 512) if n % unit else 0 for n in sizes]
+    per_tensor = [f + r for f, r in zip(full, ragged)]
+    assert ragged == [6, 0, 0, 6, 1] and units == sum(per_tensor)
     nbytes = solo.solo_multi_table_bytes(len(sizes), units)
     assert nbytes == 96 * len(sizes) + 4 * units
     buf = np.zeros(nbytes, np.uint8)
@@ -136,7 +138,9 @@ def test_multi_tensor_table_layout(solo):
         want_ptrs = [base, base + 0x1000000 if k == 2 else 0] + [base + 0x1000000 * j for j in range(2, 8)]
         assert list(entries[k, :8]) == want_ptrs
         assert entries[k, 8] == n and entries[k, 9] == unit0 and entries[k, 10] == xi
-        assert np.all(unit_map[unit0:unit0 + per_tensor[k]] == k)
+        assert np.all(unit_map[unit0:unit0 + full[k]] == k)
+        want = [k | (c << 24) | 0x80000000 for c in range(ragged[k])]
+        assert list(unit_map[unit0 + full[k]:unit0 + per_tensor[k]]) == want
         unit0 += per_tensor[k]
         xi += -(-n // 2560) * 2560                               # xi offsets advance in 2560-element steps
     # a misaligned or missing pointer of a non-empty tensor is refused; an empty tensor's are ignored

@@ -594,7 +594,7 @@ def test_multi_tensor_table_rejects_bad_descriptors(gpu):
     arr[0] = solo.solo_tensor(p.data_ptr(), None, g.data_ptr(), st.m_codes.data_ptr(), st.m_scale.data_ptr(),
                               st.v_codes.data_ptr(), st.v_scale.data_ptr(), st.v_base.data_ptr(), n)
     units = solo.solo_multi_units(arr, 1, cfg)
-    assert units in (1, 2)                       # 3000 elements: one 5120- or two 2560-element units
+    assert units == 6                            # 3000 elements, all of them a ragged end: one unit per 512 elements
     nbytes = solo.solo_multi_table_bytes(1, units)
     assert nbytes == 96 + 4 * units
     buf = (C.c_uint8 * nbytes)()
