@@ -145,6 +145,8 @@ def main():
                     choices=("adamw", "adam_l2", "adabelief", "adamw_mp", "adabelief_mp"),
                     help="step variant: coupled decay, AdaBelief; *_mp adds the bf16 weight copy and "
                          "a gradient scale read from device memory (the default, adamw, is the metric)")
+    ap.add_argument("--eps", type=float, default=None,
+                    help="eps of the optimizer (default: the workload's 1e-8; AdaBelief variants 1e-16)")
     ap.add_argument("--launch", default="flat", choices=("flat", "multi", "per_tensor"),
                     help="flat: one call over the whole flat buffer (the metric); multi: the workload's "
                          "tensors as separate buffers in one solo_adamw_step_multi launch; per_tensor: one "
@@ -172,7 +174,8 @@ def main():
                            # AdaBelief adds eps to the 2nd EMA itself; its published default is 1e-16
                            # (1e-8 would swamp the squared residuals of these gradients and make
                            # every block constant)
-                           eps=1e-16 if args.variant.startswith("adabelief") else w.eps,
+                           eps=args.eps if args.eps is not None else
+                           (1e-16 if args.variant.startswith("adabelief") else w.eps),
                            weight_decay=w.weight_decay, quantile_p=w.quantile_p, seed=synth.SEED_XI,
                            flags=solo.SOLO_FLAG_STOCHASTIC
                            | (solo.SOLO_FLAG_M_DYNAMIC_EXPONENT if w.m_codebook == "de" else 0)

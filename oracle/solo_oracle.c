@@ -230,11 +230,19 @@ void so_xi_keys(uint64_t seed, uint64_t step, uint32_t keys[4])
     keys[2] = (uint32_t)b; keys[3] = (uint32_t)(b >> 32);
 }
 
-/* 32 uniform bits of element i.  Elements are taken in groups of eight: the
- * group index is hashed to a start X and an odd stride Y, and element j of the
- * group receives X + j*Y (mod 2^32).  The stream is a pure function of
- * (seed, step, global element index): xi is drawn independently per element
- * and per update (Sec. 3.2.2; proof of Prop. 3.4). */
+/* 32 uniform bits of element i, a pure function of (seed, step, global element
+ * index): xi is drawn independently per element and per update (Sec. 3.2.2;
+ * proof of Prop. 3.4).  The construction is that of a split-mix generator, a
+ * Weyl sequence whose terms pass through a finalizer: elements are taken in
+ * groups of eight; two strong hashes of the group index give a start X and an
+ * odd stride Y, element j of the group owns the word w = X + j*Y (mod 2^32),
+ * and its bits are w ^ (w >> 15), of which the low 24 bits (they contain every
+ * bit of w) are multiplied by an odd 24-bit constant, keeping the low 32 bits
+ * of the product.  Without the finalizer the eight words of a group would lie
+ * on one arithmetic progression: each uniform, any two independent, but any
+ * three linearly dependent (w[j+2] = 2 w[j+1] - w[j]), which shows in every
+ * joint statistic of three or more neighbours.  The tests check the joint
+ * distribution of neighbours up to all eight of a group. */
 uint32_t so_xi_bits(const uint32_t keys[4], uint64_t i)
 {
     uint64_t group = i >> 3;
@@ -242,7 +250,9 @@ uint32_t so_xi_bits(const uint32_t keys[4], uint64_t i)
     uint32_t glo = (uint32_t)group, ghi = (uint32_t)(group >> 32);
     uint32_t X = so_mix32((glo ^ keys[0]) + ghi * keys[2]);
     uint32_t Y = so_mix32(X ^ keys[1]) | 1u;
-    return X + j * Y;
+    uint32_t w = X + j * Y;
+    uint32_t t = w ^ (w >> 15);
+    return (t & 0xFFFFFFu) * 0xC2B2AFu;
 }
 
 /* xi in the open interval (-0.5, 0.5): the top 23 bits u give
@@ -252,6 +262,12 @@ float so_xi(const uint32_t keys[4], uint64_t i)
 {
     uint32_t u = so_xi_bits(keys, i) >> 9;
     return (float)u * 0x1p-23f + (0x1p-24f - 0.5f);
+}
+
+/* xi of n consecutive elements starting at global index i0. */
+void so_xi_fill(const uint32_t keys[4], uint64_t i0, uint64_t n, float *out)
+{
+    for (uint64_t k = 0; k < n; ++k) out[k] = so_xi(keys, i0 + k);
 }
 
 /* -------------------------------------------------------------- quantizers */

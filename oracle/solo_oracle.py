@@ -84,6 +84,7 @@ def _declare(L):
     L.so_xi_keys.restype = None; L.so_xi_keys.argtypes = [C.c_uint64, C.c_uint64, _u32p]
     L.so_xi_bits.restype = C.c_uint32; L.so_xi_bits.argtypes = [_u32p, C.c_uint64]
     L.so_xi.restype = C.c_float; L.so_xi.argtypes = [_u32p, C.c_uint64]
+    L.so_xi_fill.restype = None; L.so_xi_fill.argtypes = [_u32p, C.c_uint64, C.c_uint64, _f32p]
     L.so_rank.restype = C.c_uint32; L.so_rank.argtypes = [C.c_float, C.c_uint32]
     L.so_root.restype = C.c_float; L.so_root.argtypes = [C.c_float, C.c_uint32]
     L.so_quant_m_block.restype = None
@@ -156,8 +157,14 @@ def xi_bits(keys, i):
 
 
 def xi_array(seed, step, i0, count):
+    out = np.zeros(count, np.float32)
+    lib().so_xi_fill(xi_keys(seed, step), i0, count, out)
+    return out
+
+
+def xi_bits_array(seed, step, i0, count):
     keys = xi_keys(seed, step)
-    return np.array([lib().so_xi(keys, i0 + k) for k in range(count)], np.float32)
+    return np.array([lib().so_xi_bits(keys, i0 + k) for k in range(count)], np.uint32)
 
 
 # ------------------------------------------------------------- block helpers

@@ -85,11 +85,7 @@ static uint64_t mix64(uint64_t z)
 // bias corrections (binary64 on the host), the rank of the quantile, the keys of the xi stream.
 static void step_scalars(StepArgs &a, const solo_config *cfg, uint64_t step)
 {
-    a.param = nullptr; a.grad = nullptr; a.m_words = nullptr; a.m_scale = nullptr;
-    a.v_words = nullptr; a.v_scale = nullptr; a.v_base = nullptr;
-    a.param_bf16 = nullptr; a.grad_scale = nullptr;
-    a.n = 0; a.index_offset = 0;
-    a.n_tiles_full = 0; a.wg_per_xcd = 0; a.tail_tile0 = 0;   // set by the launcher of the instantiation
+    a = StepArgs{};                 // pointers, n, index_offset: the caller; the tiling: the launcher of the instantiation
     a.beta1 = cfg->beta1; a.omb1 = 1.0f - cfg->beta1;
     a.beta2 = cfg->beta2; a.omb2 = 1.0f - cfg->beta2;
     const double bc1 = 1.0 - pow((double)cfg->beta1, (double)step);

@@ -37,7 +37,7 @@
 //     candidates around a hardware exp2/log2 guess, one per lane;
 //   * codes are rounded in the float domain and accumulated with FMAs
 //     (acc = acc * 2^b + code); xi is built as a float in [1, 2) by one
-//     bit-align of the hashed word.
+//     bit-align of the element's hashed word.
 //
 // Arithmetic contract (what makes the stored bytes reproducible): every value
 // that decides a code or a scale is computed in binary32, one rounding per
@@ -218,6 +218,22 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h)
     h ^= h >> 16;
     return h;
 }
+
+// Finalizer of an element's word of the xi stream: the group's words X + j Y lie on an arithmetic
+// progression; xorshift and one 24-bit multiplication (full rate; the low 24 bits of the
+// xorshifted word contain every bit of w) make the eight elements of a group jointly independent.
+constexpr uint32_t kXiMul = 0xC2B2AFu;
+__host__ __device__ constexpr uint32_t xi_finalize_ref(uint32_t w)
+{
+    return ((w ^ (w >> 15)) & 0xFFFFFFu) * kXiMul;
+}
+__device__ __forceinline__ uint32_t xi_finalize(uint32_t w)
+{
+    return __umul24(w ^ (w >> 15), kXiMul);
+}
+// A word whose finalized top 23 bits are 100...0, i.e. xi = 0 (deterministic rounding).
+constexpr uint32_t kXiZeroWord = 0x1B29A9u;
+static_assert((xi_finalize_ref(kXiZeroWord) >> 9) == 0x400000u, "xi = 0 word");
 
 // Level alpha^q of the log codebook for a run-time q, by binary powering in the
 // dequantizer's fixed order: the selected powers a, a^2, a^4, a^8 are
@@ -641,25 +657,28 @@ __device__ __forceinline__ void store_state_image(const StepArgs &a, uint64_t ti
 // loop's back edge as its only branch.  A lane keeps the key behind its head in a register: a pop
 // moves it up and fetches the one after it, whose LDS latency then lies outside the chain of
 // rounds (it is waited for only when the same lane pops again).  A scalar population count
-// detects the rounds in which two lanes of a group tie; then only the lowest holder pops, so
-// exactly one key leaves a group per round.
+// detects the rounds in which two lanes of a group tie; then only the lowest holder of a group
+// pops, so exactly one key leaves a group per round: a lane counts the holders below it in the
+// wavefront (two mbcnt), the count of the group's first lane is spread over the group by DPP,
+// and the lowest holder is the one whose count equals it.  A few vector instructions, no loop
+// over the groups and no register that lives across the rounds.
 template <int G>
 __device__ __forceinline__ uint32_t extract_rth(uint32_t head, uint32_t behind, uint32_t haddr, uint32_t rank)
 {
     constexpr int NG = 64 / G;
-    constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : (1u << (G & 15)) - 1u;
     uint32_t xp_bits = 0;
     for (uint32_t k = 0; k < rank; ++k) {
         const uint32_t mn = group_reduce<G>(head, UMin());
         uint64_t holders = __builtin_amdgcn_ballot_w64(head == mn);
         if (__builtin_expect(__builtin_popcountll(holders) != NG, 0)) {
-            uint64_t lowest = 0;
-#pragma unroll
-            for (int gi = 0; gi < NG; ++gi) {
-                const uint64_t f = (holders >> (gi * G)) & (uint64_t)GMASK;
-                lowest |= (f & (0 - f)) << (gi * G);
-            }
-            holders = lowest;
+            const uint32_t c = __builtin_amdgcn_mbcnt_hi((uint32_t)(holders >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)holders, 0u));
+            uint32_t c0 = dpp<0x00>(c);                     // quad_perm [0,0,0,0]
+            if (G >= 8)                                     // lanes 4-7 and 12-15 of a row <- four lanes down
+                c0 = (uint32_t)__builtin_amdgcn_update_dpp((int)c0, (int)c0, 0x114, 0xF, 0xA, false);
+            if (G == 16)                                    // lanes 8-15 of a row <- eight lanes down
+                c0 = (uint32_t)__builtin_amdgcn_update_dpp((int)c0, (int)c0, 0x118, 0xF, 0xC, false);
+            holders &= __builtin_amdgcn_ballot_w64(c == c0);
         }
         xp_bits = mn;
         uint64_t saved;
@@ -705,10 +724,17 @@ __device__ __forceinline__ BlockCodec block_codec(uint32_t xp_bits, float dm, fl
     BlockCodec c = {inv_s, 1.0f, 0.0f, 0.0f, 1.0f};
     const bool need = rho < 1.0f;
     const uint32_t ab = search_base<BV, G>(rho, need, lane, lig, gshift);
+    // the two reciprocals of the 2nd-moment encoder, correctly rounded, again by one shared
+    // division: 1 / log2(alpha) on the even lanes, 1 / Delta_v on the odd ones (a block that
+    // does not need them divides by harmless stand-ins)
+    const float den2 = (lane & 1u) ? (need ? dv : 1.0f) : __builtin_amdgcn_logf(need ? u2f(ab) : 0.5f);
+    const float quo2 = 1.0f / den2;
+    const float inv_l2a = u2f(dpp<0xA0>(f2u(quo2)));
+    const float rdv = u2f(dpp<0xF5>(f2u(quo2)));
     if (need) {
         c.alpha = u2f(ab);
-        c.inv_l2a = __builtin_amdgcn_rcpf(__builtin_amdgcn_logf(c.alpha));
-        c.rdv = __builtin_amdgcn_rcpf(dv);
+        c.inv_l2a = inv_l2a;
+        c.rdv = rdv;
         c.bias = 0.0f;
     }
     return c;
@@ -716,8 +742,9 @@ __device__ __forceinline__ BlockCodec block_codec(uint32_t xp_bits, float dm, fl
 
 // Encodes a lane's run of 8 consecutive elements starting at global element index e (a multiple
 // of 8): returns the packed 1st- and 2nd-moment codes (element j in bits [b j, b j + b)).
-// xi: one hashed start and stride per 8 elements; 1.5 + xi - 2^-24 is built as a float in [1,2)
-// by one bit-align of the hashed word.  Codes are rounded in the float domain, four to an
+// xi: one hashed start and stride per 8 elements, every element's word finalized on its own;
+// 1.5 + xi - 2^-24 is built as a float in [1,2) by one bit-align of the finalized word.
+// Codes are rounded in the float domain, four to an
 // accumulator: m: code - L = rint(m^ * L/Delta_m) in [-L, L];
 // v: code + 1 = floor(log_alpha(v^/Delta_v) + 1.5 + xi).  `ok` (TAIL only): the elements that exist.
 template <int BM, int BV, bool MDE, bool TAIL>
@@ -731,7 +758,7 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
     const uint64_t gidx = (a.index_offset + e) >> 3;
     uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
     uint32_t Y = mix32(X ^ a.key1) | 1u;
-    if (!a.stochastic) { X = 0x80000000u; Y = 0u; }     // xi = 0: the float is 1.5
+    if (!a.stochastic) { X = kXiZeroWord; Y = 0u; }     // xi = 0: the float is 1.5
     uint32_t xj = X + ((Y << 3) - Y);                   // X + j Y, walked down from j = 7
     float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
     uint32_t m8_de = 0;
@@ -765,7 +792,7 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
             if (TAIL && !ok[j]) code = 0;
             m8_de |= code << (BM * j);
         }
-        const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, xj, 9u));
+        const float f = u2f(__builtin_amdgcn_alignbit(0x7Fu, xi_finalize(xj), 9u));
         const float ratio = __builtin_fmaf(vh[j], c.rdv, c.bias);
         float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), c.inv_l2a, f));
         tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));   // +inf (v^ = 0) takes the last code

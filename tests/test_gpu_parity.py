@@ -29,6 +29,27 @@ FLIP_MARGIN = 5e-5
 FLIP_RATE = 1e-5
 
 
+# every 2nd-moment code on which the two sides disagreed, over the whole module run:
+# (oracle margin in code units, |log2 alpha| of the block); written to gpurun_out/flip_margins.txt
+FLIP_LOG = []
+CODES_COMPARED = [0]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def flip_report():
+    yield
+    import os
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    os.makedirs(out, exist_ok=True)
+    with open(os.path.join(out, "flip_margins.txt"), "w") as f:
+        f.write(f"# codes compared: {CODES_COMPARED[0]}, flips: {len(FLIP_LOG)}\n# margin  |log2 alpha|  margin*|log2 alpha|*2^23\n")
+        for m, l in sorted(FLIP_LOG, key=lambda t: -t[0]):
+            f.write(f"{m:.4g} {l:.4g} {m * l * 2 ** 23:.3g}\n")
+    well = [m for m, l in FLIP_LOG if l > 0.01]
+    print(f"\nflips: {len(FLIP_LOG)} in {CODES_COMPARED[0]} codes; largest margin with |log2 alpha| > 0.01: "
+          f"{max(well) if well else 0:.3g}")
+
+
 def flip_budget(codes):
     """Flips tolerated among `codes` compared codes: the 1e-5 rate as a mean, with room for its
     Poisson scatter (every single flip has already been checked against its margin)."""
@@ -142,7 +163,10 @@ def compare_step(so, oc, n, want_p, want_st, margin, got, p_rtol, p_atol, tainte
         assert np.array_equal(gm, want_st.m_words), "1st-moment words differ (pad bits?)"
     diff = np.nonzero((hv != wv) & eclean)[0]
     n_flips = 0
+    CODES_COMPARED[0] += int(eclean.sum())
     if diff.size:
+        l2a_all = np.abs(np.log2(np.minimum(np.repeat(want_st.v_base, B)[:n].astype(np.float64), 1.0 - 2.0 ** -25)))
+        FLIP_LOG.extend(zip(margin[diff].tolist(), l2a_all[diff].tolist()))
         d = np.abs(hv[diff].astype(int) - wv[diff].astype(int))
         assert d.max() == 1, f"2nd-moment code off by {d.max()} at {diff[np.argmax(d)]}"
         allow = flip_allowance(np.repeat(want_st.v_base, B)[:n])

@@ -288,6 +288,95 @@ def test_xi_stream_is_uniform_and_uncorrelated(so):
     assert so.xi(so.xi_keys(42, 1), 12345) == np.float32(a[12345])
 
 
+def test_xi_neighbours_are_jointly_independent(so):
+    """Sec. 3.2.2 draws xi independently per element.  The stream takes elements in groups of
+    eight that share one hashed start and stride; what separates the eight is the finalizer of
+    every element's word.  Checked here on what a shared start and stride would spoil: the joint
+    distribution of three and four neighbours, the pattern of all eight against a threshold,
+    and the three-term relation of an arithmetic progression, inside and across groups."""
+    groups = 1 << 18
+    x = so.xi_array(7, 3, 8 * 12345, 8 * groups).astype(np.float64).reshape(groups, 8) + 0.5
+
+    def chi2(cells, expected):
+        return float(np.sum((cells - expected) ** 2 / expected))
+
+    for tup in ((0, 1, 2), (2, 3, 4), (0, 3, 7), (5, 6, 7)):                 # triples, 8^3 cells
+        idx = sum(np.floor(x[:, t] * 8).astype(int) * 8 ** k for k, t in enumerate(tup))
+        assert chi2(np.bincount(idx, minlength=512), groups / 512) < 511 + 6 * math.sqrt(2 * 511), tup
+    for tup in ((0, 1, 2, 3), (1, 2, 6, 7), (4, 5, 6, 7)):                    # quadruples, 5^4 cells
+        idx = sum(np.floor(x[:, t] * 5).astype(int) * 5 ** k for k, t in enumerate(tup))
+        assert chi2(np.bincount(idx, minlength=625), groups / 625) < 624 + 6 * math.sqrt(2 * 624), tup
+    for q in (0.5, 0.25, 0.1):                                               # all eight against a threshold
+        pat = ((x >= 1 - q).astype(int) << np.arange(8)).sum(1)
+        ones = np.array([bin(k).count("1") for k in range(256)])
+        expected = groups * q ** ones * (1 - q) ** (8 - ones)
+        keep = expected > 5
+        assert chi2(np.bincount(pat, minlength=256)[keep], expected[keep]) < keep.sum() + 6 * math.sqrt(2 * keep.sum()), q
+    # no arithmetic progression: x[j+2] - 2 x[j+1] + x[j] = 0 (mod 2^32) for essentially no triple
+    w = so.xi_bits_array(7, 3, 0, 8 * 4096).astype(np.int64).reshape(-1)
+    second = (w[2:] - 2 * w[1:-1] + w[:-2]) % (1 << 32)
+    assert np.mean(second == 0) < 1e-3
+    assert len(np.unique(w)) > 0.999 * w.size
+
+
+def test_decay_of_a_block_in_one_state_is_binomial(so):
+    """What the independence is for (Prop. 3.4): when the 128 elements of a block sit in one
+    state alpha^k and receive zero signals with alpha = beta^c, every element drops a level with
+    probability 1/c on its own, so the number that drop per update is Binomial(128, 1/c): mean,
+    variance, third central moment, and the distribution of the count inside each group of
+    eight neighbours."""
+    blocks, bits = 40000, 3
+    for c, step in ((2, 1), (3, 2), (10, 3)):
+        beta = 0.9
+        alpha = np.float32(beta ** c)
+        q = 1.0 / c
+        x = np.float32(beta * float(so.log_level(alpha, 2, bits)))          # one EMA step from level 2, Delta = 1
+        xi = so.xi_array(99, step, 128 * 777, 128 * blocks)
+        # the decision of the log quantizer for this x as a threshold on xi (checked on a sample)
+        t = math.log2(float(x)) / math.log2(float(alpha))
+        drops = xi.astype(np.float64) + t >= 2.5
+        sample = slice(0, 4096)
+        codes = np.array([so.quant_v_elem(x, 1.0, alpha, float(e), bits) for e in xi[sample]])
+        assert np.array_equal(codes == 3, drops[sample]) and set(np.unique(codes)) <= {2, 3}
+        cnt = drops.reshape(blocks, 128).sum(1).astype(np.float64)
+        mean, var, m3 = 128 * q, 128 * q * (1 - q), 128 * q * (1 - q) * (1 - 2 * q)
+        assert abs(cnt.mean() - mean) < 5 * math.sqrt(var / blocks)
+        assert abs(cnt.var() / var - 1) < 5 * math.sqrt(2 / blocks)
+        m6 = 15 * var ** 3                                                  # sixth moment, normal approximation
+        assert abs(((cnt - cnt.mean()) ** 3).mean() - m3) < 6 * math.sqrt(m6 / blocks)
+        c8 = drops.reshape(-1, 8).sum(1)
+        expected = c8.size * np.array([math.comb(8, k) * q ** k * (1 - q) ** (8 - k) for k in range(9)])
+        keep = expected > 5
+        got = np.bincount(c8, minlength=9)
+        chi = float(np.sum((got[keep] - expected[keep]) ** 2 / expected[keep]))
+        assert chi < keep.sum() + 6 * math.sqrt(2 * keep.sum()), (c, chi)
+
+
+def test_decay_of_sums_over_neighbours(so):
+    """Prop. 3.4 over many updates, on sums over eight neighbouring elements: with alpha = beta^c,
+    zero signals and a fixed scale, an element's level index grows by one with probability 1/c
+    per update, independently of its neighbours and of the past.  After T updates the sum of the
+    eight indices of a group has mean 8 (k0 + T/c) and variance 8 T (1/c)(1 - 1/c)."""
+    beta, c, bits, T, groups = 0.95, 4, 4, 20, 20000
+    alpha = np.float32(beta ** c)
+    code = np.full(8 * groups, 1, np.int64)
+    levels = np.array([float(so.log_level(alpha, k, bits)) for k in range(16)])
+    for t in range(1, T + 1):
+        xi = so.xi_array(5, t, 0, code.size)
+        x = (np.float32(beta) * levels[code].astype(np.float32)).astype(np.float32)
+        pos = np.log2(x.astype(np.float64)) / math.log2(float(alpha)) + xi           # log-domain position + xi
+        new = np.clip(np.rint(pos), 0, 15).astype(np.int64)
+        if t in (1, T):                                                               # the oracle's own decision on a sample
+            for i in range(0, code.size, 997):
+                assert new[i] == so.quant_v_elem(float(x[i]), 1.0, alpha, float(xi[i]), bits)
+        assert np.all((new == code) | (new == code + 1))
+        code = new
+    sums = code.reshape(groups, 8).sum(1).astype(np.float64)
+    var = 8 * T * (1 / c) * (1 - 1 / c)
+    assert abs(sums.mean() - 8 * (1 + T / c)) < 5 * math.sqrt(var / groups)
+    assert abs(sums.var() / var - 1) < 5 * math.sqrt(2 / groups)
+
+
 # ------------------------------------------------------------------ packing
 
 def test_pack_layout_literals(so):
