@@ -38,9 +38,12 @@ def bytes_per_param(w):
     return (4 + g + codes + scales) + (4 + codes + scales)
 
 
-def device_grads(torch, n, kind, std, seed, dtype):
+def device_grads(torch, n, kind, std, seed, dtype, sparse_rows=None):
     """Seeded synthetic gradients generated on the device, chunk by chunk (same recipe as
-    synth.make_grads: N(0, std^2), Student-t(3) * std, or normal with 1 % of entries x100)."""
+    synth.make_grads: N(0, std^2), Student-t(3) * std, or normal with 1 % of entries x100).
+    sparse_rows = (first element, rows, row length, zero fraction): that many rows of that
+    matrix, drawn afresh with the same seed, are set to zero (the embedding rows of tokens that
+    do not occur in a batch)."""
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
     out = torch.empty(n, dtype=dtype, device="cuda")
@@ -55,7 +58,21 @@ def device_grads(torch, n, kind, std, seed, dtype):
             chi = torch.randn(3, b - a, device="cuda", generator=gen).square_().sum(0).div_(3.0).sqrt_()
             x = x / chi
         out[a:b] = (x * std).to(dtype)
+    if sparse_rows is not None:
+        first, rows, row_len, zero_frac = sparse_rows
+        idle = torch.rand(rows, device="cuda", generator=gen) < zero_frac
+        out[first:first + rows * row_len].view(rows, row_len)[idle] = 0
     return out
+
+
+def sparse_rows_of(w):
+    """The sparse_rows argument of device_grads for a workload (None: dense gradients)."""
+    sp = w.extra.get("sparse_rows")
+    if not sp:
+        return None
+    first = sum(t[1] for t in w.tensors[:sp["tensor"]])
+    numel = w.tensors[sp["tensor"]][1]
+    return (first, numel // sp["row_len"], sp["row_len"], sp["zero_frac"])
 
 
 def device_params(torch, w, seed):
@@ -191,7 +208,7 @@ def main():
         def __init__(self):
             self.p = device_params(torch, w, synth.SEED_PARAM)
             self.grads = [device_grads(torch, n, w.grad_kind, w.grad_std,
-                                       synth.seed_grad(w.config_id, k), gdtype) for k in (1, 2)]
+                                       synth.seed_grad(w.config_id, k), gdtype, sparse_rows_of(w)) for k in (1, 2)]
             self.extras = {}
             if mp:
                 self.extras = {"param_bf16": torch.empty(n, dtype=torch.bfloat16, device="cuda"),

@@ -111,6 +111,11 @@ def workload(name):
     if name == "paper_2bit_llama7b":
         return Workload(name, 7, llama_7b_shapes(), 2, 2, 128, 0.5, "bf16", "normal_outliers", 1e-4,
                         m_codebook="de")
+    # C5 with the sparse-embedding stress of Sec. 3.2.2: per step, 90 % of the rows of the
+    # embedding matrix (the first tensor) receive no gradient at all
+    if name == "c5_sparse_embed":
+        return Workload(name, 5, llama_7b_shapes(), 2, 3, 128, 0.5, "bf16", "normal_outliers", 1e-4,
+                        extra={"sparse_rows": {"tensor": 0, "row_len": 4096, "zero_frac": 0.9}})
     raise KeyError(name)
 
 
@@ -154,6 +159,12 @@ def make_grads(n, kind, std, seed, stream=0):
     else:
         raise KeyError(kind)
     return (x * np.float32(std)).astype(np.float32)
+
+
+def zero_row_mask(rows, zero_frac, seed, stream=0):
+    """Which rows of an embedding-shaped matrix receive no gradient in one step (True = all
+    zeros): each row independently with probability zero_frac, fresh per (seed, stream)."""
+    return _rng(seed ^ 0x5EED, stream).random(rows, np.float32) < np.float32(zero_frac)
 
 
 def workload_slice(w, step, count=None, tensor_index=0):
