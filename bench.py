@@ -95,8 +95,9 @@ def device_params(torch, w, seed):
 
 
 def cpu_baseline(w, sample, steps=3):
-    """The CPU oracle, as it stands, on the first `sample` elements of the workload's largest
-    tensor class, all host threads, median of the timed steps."""
+    """The CPU oracle, as it stands, on the first `sample` elements of the workload's first
+    tensor: with all host threads (median of the timed steps), and with one thread on an eighth
+    of that sample."""
     import numpy as np
     from oracle import solo_oracle as so
     from paper_2505_00347_amd import synth
@@ -105,21 +106,28 @@ def cpu_baseline(w, sample, steps=3):
                          beta2=w.beta2, lr=w.lr, eps=w.eps, weight_decay=w.weight_decay,
                          quantile_p=w.quantile_p, seed=synth.SEED_XI,
                          m_codebook=1 if w.m_codebook == "de" else 0)
-    p = synth.make_params(sample)
-    st = so.State(sample, cfg)
-    times = []
-    for step in range(1, steps + 1):
-        g = synth.make_grads(sample, w.grad_kind, w.grad_std, synth.seed_grad(w.config_id, step))
-        if w.grad_dtype == "bf16":
-            g = synth.round_to_bf16(g)[1]
-        t0 = time.perf_counter()
-        so.step_packed(p, g, st, step, cfg, threads=threads)
-        times.append(time.perf_counter() - t0)
-    t = float(np.median(times[1:])) if len(times) > 1 else times[0]
-    return {"value": sample / t, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {sample} elements of the workload (one contiguous slice, packed "
-                      f"states, {steps} steps, median of steps 2..{steps}); the step is block-local, "
-                      "so the rate carries over to the full tensor set"}
+
+    def rate(count, nthreads):
+        p = synth.make_params(count)
+        st = so.State(count, cfg)
+        times = []
+        for step in range(1, steps + 1):
+            g = synth.make_grads(count, w.grad_kind, w.grad_std, synth.seed_grad(w.config_id, step))
+            if w.grad_dtype == "bf16":
+                g = synth.round_to_bf16(g)[1]
+            t0 = time.perf_counter()
+            so.step_packed(p, g, st, step, cfg, threads=nthreads)
+            times.append(time.perf_counter() - t0)
+        t = float(np.median(times[1:])) if len(times) > 1 else times[0]
+        return count / t
+
+    what = (f"first %d elements of the workload (one contiguous slice, packed states, {steps} steps, "
+            f"median of steps 2..{steps}); the step is block-local, so the rate carries over to the "
+            "full tensor set")
+    small = max(sample // 8, min(sample, 1 << 20))
+    return {"value": rate(sample, threads), "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": what % sample,
+            "single_thread": {"value": rate(small, 1), "unit": "params/s", "cores": 1, "sample": what % small}}
 
 
 def stream_probe(n):
@@ -169,8 +177,12 @@ def main():
                          "tensors as separate buffers in one solo_adamw_step_multi launch; per_tensor: one "
                          "solo_adamw_step call per tensor")
     ap.add_argument("--placements", type=int, default=5,
-                    help="allocate the workload this many times and keep the allocation on which the "
-                         "warm-up steps ran fastest (1: take the first allocation as it comes)")
+                    help="allocate the workload this many times, time the warm-up steps on each and "
+                         "measure on the one --placement-policy picks (1: the first allocation as it comes)")
+    ap.add_argument("--placement-policy", default="median", choices=("median", "best", "first"),
+                    help="which of the allocations the timed steps run on: the one whose warm-up "
+                         "time is the median of all (the default: what a caller gets on a typical "
+                         "allocation), the fastest, or the first")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
@@ -255,9 +267,11 @@ def main():
             return [s.elapsed_time(e) for s, e in zip(starts, ends)]
 
     # Where the buffers land in physical HBM changes the rate this machine delivers for identical code
-    # by several percent (first allocations of a process tend to land badly).  The state of an
-    # optimizer lives for a whole training job, so it pays to pick its placement once: allocate
-    # the workload up to --placements times, warm each up, keep the fastest, free the others.
+    # by several percent.  The workload is therefore allocated up to --placements times (every
+    # candidate held until the choice is made), each allocation is warmed up and timed, and the
+    # timed steps run on the allocation whose time is the median of the candidates (policy
+    # "median", the headline: a typical allocation); the times of all candidates, and the
+    # roofline fractions of the first and of the fastest, are reported beside it.
     cands, trial_ms = [], []
     trials = max(args.warmup, 2) if args.placements > 1 else args.warmup
     for k in range(max(1, args.placements)):
@@ -269,7 +283,8 @@ def main():
         ms = r.run(trials)
         cands.append(r)
         trial_ms.append(sorted(ms[-2:])[0] if ms else None)
-    chosen = 0 if trial_ms[0] is None else min(range(len(cands)), key=lambda k: trial_ms[k])
+    order = list(range(len(cands))) if trial_ms[0] is None else sorted(range(len(cands)), key=lambda k: trial_ms[k])
+    chosen = {"median": order[(len(order) - 1) // 2], "best": order[0], "first": 0}[args.placement_policy]
     res = cands[chosen]
     del cands, r
     torch.cuda.empty_cache()
@@ -292,6 +307,10 @@ def main():
     ms_per_step = wall / args.steps * 1e3
     bpp = bytes_per_param(w) + (2.0 if mp else 0.0)      # the bf16 copy is two more bytes written
     achieved = bpp * n / avg_kernel_s / 1e9
+
+    def frac_of(ms):
+        return (bpp * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if ms else None
+
     out = {
         "metric": "updated_params_per_sec", "value": n / (wall / args.steps), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -306,10 +325,12 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name) if (args.variant, args.launch) == ("adamw", "flat") else None,
                      "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3,
                      "stream_probe": probe},
-        # (frac_first: what the roofline fraction would be on the first allocation as it came,
-        # from its warm-up steps)
-        "placement": {"candidates_ms": trial_ms, "chosen": chosen,
-                      "frac_first": (bpp * n / (trial_ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBS) if trial_ms[0] else None},
+        # the warm-up time of every allocation that was tried, which one the timed steps ran on, and
+        # the roofline fraction the warm-up steps gave on the first and on the fastest of them
+        "placement": {"policy": args.placement_policy if len(trial_ms) > 1 else "first",
+                      "candidates_ms": trial_ms, "chosen": chosen,
+                      "frac_first": frac_of(trial_ms[0]), "frac_best": frac_of(trial_ms[order[0]]),
+                      "frac_median": frac_of(trial_ms[order[(len(order) - 1) // 2]])},
     }
     del res, p
     torch.cuda.empty_cache()

@@ -38,6 +38,9 @@
  *   is no level -1).  A 2nd-moment code q in [0, 2^bits_v - 1] stands for alpha^q.
  *   param, grad and the code buffers must be 16-byte aligned, the scale
  *   buffers 4-byte aligned.
+ *   The unused bits of the code words (the two pad bits of every 3-bit word, the
+ *   fields behind element n-1 of the last word) must be zero on entry to a step;
+ *   solo_state_init and every step leave them zero.
  */
 #ifndef SOLO_H
 #define SOLO_H
@@ -91,10 +94,15 @@ typedef struct solo_config {
 } solo_config;
 
 /* Number of uint32 words that hold n codes of the given width (2, 3 or 4);
- * 0 for an unsupported width. */
+ * 0 for an unsupported width.  Sec. 3.4 packs several low-bit codes into one
+ * storage element (two 4-bit or four 2-bit codes per byte; a word of this library
+ * is four such bytes, little-endian); 3-bit codes, which Sec. 3.4 leaves out for
+ * lack of a packing, go ten to a word with two unused bits. */
 size_t solo_code_words(uint64_t n, uint32_t bits);
 
-/* ceil(n / block_size); 0 if block_size is 0. */
+/* Number of quantization blocks of n elements, ceil(n / block_size) (block-wise
+ * quantization, Sec. 3.4: every block of block_size consecutive elements has its
+ * own scale; a shorter last block is a block of its own); 0 if block_size is 0. */
 size_t solo_num_blocks(uint64_t n, uint32_t block_size);
 
 /* Bytes of optimizer state for n elements: both code buffers plus three
@@ -111,8 +119,12 @@ float solo_beta1_default(uint32_t bits_m, int from_scratch);
  * (Sec. 3.3, Eq. "beta-prime"), given the two median radii. */
 float solo_beta1_bound(float beta, float r_median_b, float r_median_bprime);
 
-/* Write the zero state: every 1st-moment code = L (level 0), every
- * 2nd-moment code = 0, Delta_m = Delta_v = 0, alpha = 1. */
+/* Write the zero state m = v = 0 of a fresh optimizer.  The paper does not say how
+ * the zero state is encoded; this library's reading: every 1st-moment code = L (the
+ * code of level 0 of either codebook, not a zero byte), every 2nd-moment code = 0,
+ * Delta_m = Delta_v = 0, alpha = 1 (a block whose maximum is zero has no levels to
+ * tell apart; the step treats Delta = 0 as "all elements are exactly 0").  Unused
+ * bits of the code words are written as zeros. */
 int solo_state_init(uint32_t *m_codes, float *m_scale,
                     uint32_t *v_codes, float *v_scale, float *v_base,
                     uint64_t n, const solo_config *cfg, void *stream);
