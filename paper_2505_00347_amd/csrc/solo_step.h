@@ -545,6 +545,22 @@ struct SlabLayout {
 #ifndef SOLO_WIDE
 #define SOLO_WIDE 1
 #endif
+// Up to how many elements a flat buffer runs one wavefront per 512-element iteration instead of
+// one per super-tile.  Measured on MI355X (per-call time over sizes from 2^12 to 2^29, every
+// format): the one-iteration wavefronts need 57 registers and run seven to a SIMD, which hides
+// the memory latency without any software prefetch, so a tensor of 2^20 elements takes 9 us
+// instead of 22-30, and they stay ahead of the streaming kernels up to about 2^26 elements.
+// With fp32 gradients and the linear codebook they stay ahead at every size (2-7 % at 2^28
+// elements: the streaming kernels of these formats sit at the register limit); with bf16
+// gradients or the dynamic-exponent codebook the streaming kernels win beyond 2^26 by 2-18 %.
+#ifndef SOLO_MID_ELEMS
+#define SOLO_MID_ELEMS (64ull << 20)
+#endif
+template <bool BF16, bool MDE>
+constexpr uint64_t chunked_up_to()
+{
+    return (!BF16 && !MDE) ? ~0ull : (uint64_t)SOLO_MID_ELEMS;
+}
 #ifndef SOLO_WIDE_B64
 #define SOLO_WIDE_B64 1
 #endif
@@ -814,15 +830,17 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
 // bucket table.
 // EXT: the code that also serves the variants of the step (gradient scale, coupled decay,
 // AdaBelief, bf16 weight copy); the plain AdamW step runs the one without them.
-template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT, int TILE>
+template <int BM, int BV, int B, bool BF16, bool MDE, bool TAIL, bool EXT, int TILE, bool ALONE = TAIL>
 __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile, const uint32_t lane,
                                           uint32_t *const slab, const uint32_t *const lds_de, const int chunk = -1)
 {
-    // chunk >= 0 (TAIL only): this wavefront runs iteration `chunk` of the tile alone, next to
-    // other wavefronts that run the other iterations.  It stages the tile's state for reading and
+    // ALONE: this wavefront runs iteration `chunk` of the tile alone, next to other wavefronts
+    // that run the other iterations (short and mid-size tensors, whose super-tiles are too few to
+    // fill the machine; always so for a ragged end).  It stages the tile's state for reading and
     // applies its code changes to the global words directly (atomic XOR: the fields that
     // different wavefronts own in a shared word are disjoint) instead of writing the tile back.
-    const bool alone = TAIL && chunk >= 0;
+    static_assert(ALONE || !TAIL, "a ragged end is always cut into its iterations");
+    constexpr bool alone = ALONE;
     constexpr int G = B / 8;                       // lanes per block
     constexpr int NG = 64 / G;                     // blocks per iteration
     constexpr int kTile = TILE;
@@ -1103,7 +1121,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         const uint32_t xm1 = (BM == 3) ? (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30) : 0u;
         const uint32_t xv0 = (BV == 3) ? (xv << (3u * sv)) & 0x3FFFFFFFu : xv << (BV * sv);
         const uint32_t xv1 = (BV == 3) ? (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30) : 0u;
-        if (TAIL && alone) {
+        if (alone) {
             const uint64_t gm = tile * MW + wm, gv = tile * VW + wv;
             if (xm0 != 0u && gm < m_total) atomicXor(&a.m_words[gm], xm0);
             if (BM == 3 && xm1 != 0u && gm + 1 < m_total) atomicXor(&a.m_words[gm + 1], xm1);
@@ -1126,9 +1144,11 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     // ---- write the super-tile's state back (coalesced)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (!TAIL) {
+    if (alone) {
+        // nothing left to write
+    } else if (!TAIL) {
         store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
-    } else if (!alone) {
+    } else {
         for (uint32_t w = lane; w < MW; w += 64) {
             const uint64_t gw = tile * MW + w;
             if (gw < m_total) a.m_words[gw] = img_m[w];
@@ -1499,12 +1519,19 @@ void step_kernel(const StepArgs a)
     // run at the same time on one XCD stream through one narrow address window.
     const uint64_t wg = (uint64_t)(blockIdx.x & (kXcds - 1)) * a.wg_per_xcd + (blockIdx.x / kXcds);
     if (TAIL) {
-        // the ragged end: one wavefront per 512-element iteration of its 2560-element units
+        // one wavefront per 512-element iteration of the 2560-element units from tail_tile0 on:
+        // the ragged end of a large buffer, or the whole of a short or mid-size one.  A unit that
+        // lies inside the buffer runs the code without bounds checks.
         constexpr int kChunks = kTileUnit / kIter;
         const uint64_t c = (uint64_t)blockIdx.x * kWaves + wave;
         if (c >= a.tail_chunks) return;
-        step_tile<BM, BV, B, BF16, MDE, true, EXT, kTileUnit>(a, a.tail_tile0 + c / kChunks, lane,
-                                                              lds_slab + wave * Lay::kSlab, lds_de, (int)(c % kChunks));
+        const uint64_t unit = a.tail_tile0 + c / kChunks;
+        if ((unit + 1) * kTileUnit <= a.n)
+            step_tile<BM, BV, B, BF16, MDE, false, EXT, kTileUnit, true>(a, unit, lane, lds_slab + wave * Lay::kSlab,
+                                                                         lds_de, (int)(c % kChunks));
+        else
+            step_tile<BM, BV, B, BF16, MDE, true, EXT, kTileUnit>(a, unit, lane, lds_slab + wave * Lay::kSlab,
+                                                                  lds_de, (int)(c % kChunks));
         return;
     }
     const uint64_t tile = wg * kWaves + wave;
@@ -1566,9 +1593,10 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
 {
     StepArgs args = args_in;                   // the tiling belongs to the instantiation
     constexpr int kTile = tile_elems<BM, BV, B, MDE>();
-    // A short tensor is all latency: up to four units (a norm or bias vector) go to the kernel of
-    // the ragged end as a whole, one wavefront per 512 elements, instead of one per super-tile.
-    const bool small = args.n <= 4 * (uint64_t)kTileUnit;
+    // A short or mid-size tensor is all latency: its super-tiles would be too few to fill the
+    // machine (a wavefront walks a super-tile in 5 or 10 dependent iterations), so it goes as a
+    // whole, in one launch, to the kernel of the ragged end: one wavefront per 512 elements.
+    const bool small = args.n <= chunked_up_to<BF16, MDE>();
     args.n_tiles_full = small ? 0 : args.n / kTile;
     args.wg_per_xcd = ((args.n_tiles_full + kWaves - 1) / kWaves + kXcds - 1) / kXcds;
     const bool has_tail = small ? args.n != 0 : (args.n % kTile) != 0;
@@ -1580,6 +1608,7 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
     const bool ext = args.param_bf16 || args.grad_scale || args.belief || args.l2 != 0.0f;
     if (args.n_tiles_full) {
         const uint64_t grid = args.wg_per_xcd * kXcds;
+        if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
         if (ext)
             hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, false, true>), dim3((uint32_t)grid), dim3(kWaves * 64), 0, stream, args);
         else
@@ -1588,6 +1617,7 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
         if (e != hipSuccess) return e;
     }
     if (has_tail) {                            // the ragged end: one wavefront per 512 elements, always the full-featured kernel
+        if ((args.tail_chunks + kWaves - 1) / kWaves > 0x7FFFFFFFull) return hipErrorInvalidValue;
         const uint32_t tail_groups = (uint32_t)((args.tail_chunks + kWaves - 1) / kWaves);
         hipLaunchKernelGGL((step_kernel<BM, BV, B, BF16, MDE, true, true>), dim3(tail_groups), dim3(kWaves * 64), 0, stream, args);
         hipError_t e = hipGetLastError();
