@@ -547,20 +547,25 @@ struct SlabLayout {
 #endif
 // Up to how many elements a flat buffer runs one wavefront per 512-element iteration instead of
 // one per super-tile.  Measured on MI355X (per-call time over sizes from 2^12 to 2^29, every
-// format): the one-iteration wavefronts need 57 registers and run seven to a SIMD, which hides
-// the memory latency without any software prefetch, so a tensor of 2^20 elements takes 9 us
-// instead of 22-30, and they stay ahead of the streaming kernels up to about 2^26 elements.
-// With fp32 gradients and the linear codebook they stay ahead at every size (2-7 % at 2^28
-// elements: the streaming kernels of these formats sit at the register limit); with bf16
-// gradients or the dynamic-exponent codebook the streaming kernels win beyond 2^26 by 2-18 %.
-#ifndef SOLO_MID_ELEMS
-#define SOLO_MID_ELEMS (64ull << 20)
+// format): the one-iteration wavefronts need about 60 registers and run seven to a SIMD, which
+// hides the memory latency without any software prefetch, so a tensor of 2^20 elements takes
+// 8-9 us instead of 22-30.  With fp32 gradients and the linear codebook they stay ahead of the
+// streaming kernels at every size (by 13 % at 2^26, 5 % at 2^29 elements: the streaming kernels
+// of these formats sit at the register limit), with fp32 gradients and the dynamic-exponent
+// codebook up to 2^28; with bf16 gradients the streaming kernels take over between 2^25
+// (128-element blocks) and 2^27 elements (64-element blocks) and lead by 2-15 % at 2^29.
+#ifndef SOLO_MID_SCALE
+#define SOLO_MID_SCALE 1
 #endif
-template <bool BF16, bool MDE>
+template <int B, bool BF16, bool MDE>
 constexpr uint64_t chunked_up_to()
 {
-    return (!BF16 && !MDE) ? ~0ull : (uint64_t)SOLO_MID_ELEMS;
+    if (SOLO_MID_SCALE == 0) return 4 * (uint64_t)kTileUnit;           // (tuning builds: streaming wherever possible)
+    if (SOLO_MID_SCALE < 0) return ~0ull;                               // (tuning builds: never streaming)
+    if (!BF16) return MDE ? (256ull << 20) : ~0ull;
+    return B == 64 ? (128ull << 20) : (32ull << 20);
 }
+
 #ifndef SOLO_WIDE_B64
 #define SOLO_WIDE_B64 1
 #endif
@@ -881,32 +886,40 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     float4 *const st_c = stage + (lane + lane / 8u);        // coalesced slots: st_c[0] and st_c[72] (= slot 64 + lane)
     float4 *const st_l = stage + (2u * lane + lane / 4u);   // this lane's 8 elements: st_l[0], st_l[1]
 
-    // ---- stage the super-tile's state in LDS (coalesced; full tiles move 16 bytes per lane)
+    // ---- stage the state in LDS.  A wavefront that owns the super-tile stages all of it (coalesced,
+    // 16 bytes per lane).  One that runs a single iteration stages that iteration's part: at most
+    // 64 words of each code stream, one per lane, which the same lane writes back at the end (the
+    // first and the last 3-bit word may be shared with the neighbouring iterations' wavefronts),
+    // and the scalars of its blocks.
     static_assert(kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
-    if (!TAIL) {
-        load_state_image<BM, BV, MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
+    static_assert(kIter / 8 <= 64, "one staged word per lane and code stream");
+    uint32_t own_m = 0, own_v = 0;                 // the staged words as they were loaded
+    const uint32_t e_lo = alone ? (uint32_t)chunk * kIter : 0u, e_hi = e_lo + kIter - 1u;
+    const uint32_t wm_lo = e_lo / CM, wm_hi = e_hi / CM, wv_lo = e_lo / CV, wv_hi = e_hi / CV;
+    if (alone) {
+        const uint32_t w_m = wm_lo + lane, w_v = wv_lo + lane;
+        const uint64_t gw_m = tile * MW + w_m, gw_v = tile * VW + w_v;
+        const uint32_t b = (uint32_t)chunk * (kIter / B) + lane;
+        const uint64_t gb = tile * NBT + b;
+        const bool has_m = w_m <= wm_hi && (!TAIL || gw_m < m_total);
+        const bool has_v = w_v <= wv_hi && (!TAIL || gw_v < v_total);
+        const bool has_b = lane < (uint32_t)(kIter / B) && (!TAIL || gb < nblk);
+        // every load is issued before the first one is waited for
+        float s_dm = 0.0f, s_dv = 0.0f, s_al = 1.0f;
+        if (has_m) own_m = a.m_words[gw_m];
+        if (has_v) own_v = a.v_words[gw_v];
+        if (has_b) { s_dm = a.m_scale[gb]; s_dv = a.v_scale[gb]; s_al = a.v_base[gb]; }
+        if (BM == 3) own_m &= 0x3FFFFFFFu;
+        if (BV == 3) own_v &= 0x3FFFFFFFu;
+        if (w_m <= wm_hi) img_m[w_m] = own_m;
+        if (w_v <= wv_hi) img_v[w_v] = own_v;
+        if (lane < (uint32_t)(kIter / B)) { sc[b] = s_dm; sc[NBT + b] = s_dv; sc[2 * NBT + b] = s_al; }
+        // (a 3-bit run that ends with its word reads the word behind it without using it)
+        if (lane == 0) { img_m[wm_hi + 1] = 0; img_v[wv_hi + 1] = 0; }
     } else {
-        for (uint32_t w = lane; w < MW; w += 64) {
-            const uint64_t gw = tile * MW + w;
-            uint32_t x = gw < m_total ? a.m_words[gw] : 0u;
-            if (BM == 3) x &= 0x3FFFFFFFu;
-            img_m[w] = x;
-        }
-        for (uint32_t w = lane; w < VW; w += 64) {
-            const uint64_t gw = tile * VW + w;
-            uint32_t x = gw < v_total ? a.v_words[gw] : 0u;
-            if (BV == 3) x &= 0x3FFFFFFFu;
-            img_v[w] = x;
-        }
-        for (uint32_t b = lane; b < NBT; b += 64) {
-            const uint64_t gb = tile * NBT + b;
-            const bool ok = gb < nblk;
-            sc[b] = ok ? a.m_scale[gb] : 0.0f;
-            sc[NBT + b] = ok ? a.v_scale[gb] : 0.0f;
-            sc[2 * NBT + b] = ok ? a.v_base[gb] : 1.0f;
-        }
+        load_state_image<BM, BV, MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
     }
-    if (lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
+    if (!alone && lane < 4) { img_m[MW + lane] = 0; img_v[VW + lane] = 0; }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -1121,21 +1134,16 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         const uint32_t xm1 = (BM == 3) ? (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30) : 0u;
         const uint32_t xv0 = (BV == 3) ? (xv << (3u * sv)) & 0x3FFFFFFFu : xv << (BV * sv);
         const uint32_t xv1 = (BV == 3) ? (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30) : 0u;
+        atomicXor(&img_m[wm], xm0);
+        if (BM == 3) atomicXor(&img_m[wm + 1], xm1);
+        atomicXor(&img_v[wv], xv0);
+        if (BV == 3) atomicXor(&img_v[wv + 1], xv1);
         if (alone) {
-            const uint64_t gm = tile * MW + wm, gv = tile * VW + wv;
-            if (xm0 != 0u && gm < m_total) atomicXor(&a.m_words[gm], xm0);
-            if (BM == 3 && xm1 != 0u && gm + 1 < m_total) atomicXor(&a.m_words[gm + 1], xm1);
-            if (xv0 != 0u && gv < v_total) atomicXor(&a.v_words[gv], xv0);
-            if (BV == 3 && xv1 != 0u && gv + 1 < v_total) atomicXor(&a.v_words[gv + 1], xv1);
             if (lig == 0 && blk_ok) {
                 const uint64_t gb = tile * NBT + bl;
                 a.m_scale[gb] = dm; a.v_scale[gb] = dv; a.v_base[gb] = alpha;
             }
         } else {
-            atomicXor(&img_m[wm], xm0);
-            if (BM == 3) atomicXor(&img_m[wm + 1], xm1);
-            atomicXor(&img_v[wv], xv0);
-            if (BV == 3) atomicXor(&img_v[wv + 1], xv1);
             if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
         }
         (void)blk_ok;
@@ -1145,26 +1153,26 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     if (alone) {
-        // nothing left to write
-    } else if (!TAIL) {
-        store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
+        // Every lane writes back the word it staged.  512 two- or four-bit codes are one or two
+        // whole 128-byte lines, stored plainly.  Ten-to-a-word codes do not end on a line (or even
+        // on a word) at the end of an iteration: their words take this wavefront's changes by
+        // atomic XOR (the fields of two neighbouring iterations in a shared word are disjoint),
+        // which is carried out at the memory side and leaves no partly written line behind in
+        // the L2 of this die.
+        const uint32_t w_m = wm_lo + lane, w_v = wv_lo + lane;
+        const uint64_t gw_m = tile * MW + w_m, gw_v = tile * VW + w_v;
+        if (w_m <= wm_hi && (!TAIL || gw_m < m_total)) {
+            const uint32_t fin = img_m[w_m];
+            if (BM != 3) a.m_words[gw_m] = fin;
+            else if (fin != own_m) atomicXor(&a.m_words[gw_m], fin ^ own_m);
+        }
+        if (w_v <= wv_hi && (!TAIL || gw_v < v_total)) {
+            const uint32_t fin = img_v[w_v];
+            if (BV != 3) a.v_words[gw_v] = fin;
+            else if (fin != own_v) atomicXor(&a.v_words[gw_v], fin ^ own_v);
+        }
     } else {
-        for (uint32_t w = lane; w < MW; w += 64) {
-            const uint64_t gw = tile * MW + w;
-            if (gw < m_total) a.m_words[gw] = img_m[w];
-        }
-        for (uint32_t w = lane; w < VW; w += 64) {
-            const uint64_t gw = tile * VW + w;
-            if (gw < v_total) a.v_words[gw] = img_v[w];
-        }
-        for (uint32_t b = lane; b < NBT; b += 64) {
-            const uint64_t gb = tile * NBT + b;
-            if (gb < nblk) {
-                a.m_scale[gb] = sc[b];
-                a.v_scale[gb] = sc[NBT + b];
-                a.v_base[gb] = sc[2 * NBT + b];
-            }
-        }
+        store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
     }
 }
 
@@ -1596,7 +1604,7 @@ hipError_t launch_one(const StepArgs &args_in, hipStream_t stream)
     // A short or mid-size tensor is all latency: its super-tiles would be too few to fill the
     // machine (a wavefront walks a super-tile in 5 or 10 dependent iterations), so it goes as a
     // whole, in one launch, to the kernel of the ragged end: one wavefront per 512 elements.
-    const bool small = args.n <= chunked_up_to<BF16, MDE>();
+    const bool small = args.n <= chunked_up_to<B, BF16, MDE>();
     args.n_tiles_full = small ? 0 : args.n / kTile;
     args.wg_per_xcd = ((args.n_tiles_full + kWaves - 1) / kWaves + kXcds - 1) / kXcds;
     const bool has_tail = small ? args.n != 0 : (args.n % kTile) != 0;
