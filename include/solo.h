@@ -76,7 +76,9 @@ enum { SOLO_GRAD_FP32 = 0, SOLO_GRAD_BF16 = 1 };
 typedef struct solo_config {
     uint32_t bits_m;       /* 2, 3 or 4: signed linear or dynamic-exponent codes (App. A) */
     uint32_t bits_v;       /* 2, 3 or 4: logarithmic codes (Sec. 3.2.2)                */
-    uint32_t block_size;   /* 64 or 128 elements per block (Sec. 3.4 uses 128)         */
+    uint32_t block_size;   /* 64, 128 or 2048 elements per block (Sec. 3.4 uses 128;   */
+                           /* 2048 is the large-block setting of Sec. 4.2, flat        */
+                           /* buffers only: not in solo_adamw_step_multi)              */
     uint32_t grad_dtype;   /* SOLO_GRAD_FP32 or SOLO_GRAD_BF16                         */
     float lr;              /* learning rate                                            */
     float beta1;           /* momentum of the signed EMA, in [0,1); use the precision- */
@@ -200,7 +202,8 @@ typedef struct solo_tensor {
 /* Number of work units the tensors are cut into for cfg's state format (a unit is the 2560 or
  * 5120 elements one wavefront of that format's kernel owns; the ragged end of a tensor counts
  * one unit per 512 elements, each a wavefront of its own); 0 if cfg is invalid.  At most 2^24
- * tensors per table. */
+ * tensors per table.  Block sizes 64 and 128 only (0 for 2048; the table build and the step
+ * return SOLO_E_UNSUPPORTED). */
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg);
 
 /* Bytes of the table for `count` tensors and `units` units. */

@@ -16,7 +16,8 @@ LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libsolo.so")
 PROBE = os.path.join(LIBDIR, "stream_probe")
 SOURCES = ["solo_api.hip", "solo_step_m2.hip", "solo_step_m3.hip", "solo_step_m4.hip",
-           "solo_step_m2_de.hip", "solo_step_m3_de.hip", "solo_step_m4_de.hip"]
+           "solo_step_m2_de.hip", "solo_step_m3_de.hip", "solo_step_m4_de.hip",
+           "solo_step_big.hip", "solo_step_big_de.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off and IEEE divide/sqrt: the stored codes and scales depend on the exact
 # rounding of every operation.  Packed-FP32 instructions are disabled on the test machines.

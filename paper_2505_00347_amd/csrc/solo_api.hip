@@ -29,13 +29,24 @@ template <> hipError_t launch_multi<2, true>(uint32_t, uint32_t, bool, const Mul
 template <> hipError_t launch_multi<3, true>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
 template <> hipError_t launch_multi<4, true>(uint32_t, uint32_t, bool, const MultiArgs &, hipStream_t);
 
+template <int BM, bool MDE>
+hipError_t launch_big(uint32_t bits_v, bool bf16, const StepArgs &args, hipStream_t stream);
+template <> hipError_t launch_big<2, false>(uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_big<3, false>(uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_big<4, false>(uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_big<2, true>(uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_big<3, true>(uint32_t, bool, const StepArgs &, hipStream_t);
+template <> hipError_t launch_big<4, true>(uint32_t, bool, const StepArgs &, hipStream_t);
+
+constexpr uint32_t kLargeBlock = 2048;      // the large-block setting (one workgroup per block)
+
 static bool bits_ok(uint32_t b) { return b >= 2 && b <= 4; }
 
 static bool config_ok(const solo_config *c)
 {
     if (!c) return false;
     if (!bits_ok(c->bits_m) || !bits_ok(c->bits_v)) return false;
-    if (c->block_size != 64 && c->block_size != 128) return false;
+    if (c->block_size != 64 && c->block_size != 128 && c->block_size != kLargeBlock) return false;
     if (c->grad_dtype != SOLO_GRAD_FP32 && c->grad_dtype != SOLO_GRAD_BF16) return false;
     if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f) || !(c->beta2 >= 0.0f && c->beta2 < 1.0f)) return false;
     if (!(c->quantile_p >= 0.0f && c->quantile_p < 1.0f)) return false;
@@ -230,6 +241,15 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
     const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
+    if (cfg->block_size == solo::kLargeBlock) {
+        switch (cfg->bits_m) {
+        case 2: e = mde ? solo::launch_big<2, true>(cfg->bits_v, bf16, a, s) : solo::launch_big<2, false>(cfg->bits_v, bf16, a, s); break;
+        case 3: e = mde ? solo::launch_big<3, true>(cfg->bits_v, bf16, a, s) : solo::launch_big<3, false>(cfg->bits_v, bf16, a, s); break;
+        case 4: e = mde ? solo::launch_big<4, true>(cfg->bits_v, bf16, a, s) : solo::launch_big<4, false>(cfg->bits_v, bf16, a, s); break;
+        default: return SOLO_E_UNSUPPORTED;
+        }
+        return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;
+    }
     switch (cfg->bits_m) {
     case 2: e = mde ? solo::launch_step<2, true>(cfg->bits_v, cfg->block_size, bf16, a, s)
                     : solo::launch_step<2, false>(cfg->bits_v, cfg->block_size, bf16, a, s); break;
@@ -244,7 +264,7 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
 
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg)
 {
-    if (!tensors || !solo::config_ok(cfg)) return 0;
+    if (!tensors || !solo::config_ok(cfg) || cfg->block_size == solo::kLargeBlock) return 0;
     const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
                                                      (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
     uint64_t units = 0;
@@ -261,6 +281,7 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
                            void *table_host, size_t table_bytes, uint32_t *table_flags)
 {
     if (!solo::config_ok(cfg) || !tensors || !table_host || !table_flags || count == 0) return SOLO_E_INVALID;
+    if (cfg->block_size == solo::kLargeBlock) return SOLO_E_UNSUPPORTED;   // blocks of 2048: flat buffers only
     if (count > solo::kMapTensorMask) return SOLO_E_UNSUPPORTED;      // the map keeps the tensor index in 24 bits
     const uint64_t units = solo_multi_units(tensors, count, cfg);
     if (table_bytes < solo_multi_table_bytes(count, units)) return SOLO_E_INVALID;
@@ -302,6 +323,7 @@ int solo_adamw_step_multi(const void *table_device, uint32_t count, uint64_t uni
                           const float *grad_scale, uint64_t step, const solo_config *cfg, void *stream)
 {
     if (!solo::config_ok(cfg) || step == 0) return SOLO_E_INVALID;
+    if (cfg->block_size == solo::kLargeBlock) return SOLO_E_UNSUPPORTED;
     if (units == 0) return SOLO_OK;
     if (count == 0 || !solo::aligned(table_device, 16) || (grad_scale && !solo::aligned(grad_scale, 4)))
         return SOLO_E_INVALID;

@@ -111,6 +111,9 @@ def workload(name):
     if name == "paper_2bit_llama7b":
         return Workload(name, 7, llama_7b_shapes(), 2, 2, 128, 0.5, "bf16", "normal_outliers", 1e-4,
                         m_codebook="de")
+    # C5 with blocks of 2048 elements (the large-block setting of the block-size comparison, Sec. 4.2)
+    if name == "c5_llama7b_block2048":
+        return Workload(name, 5, llama_7b_shapes(), 2, 3, 2048, 0.5, "bf16", "normal_outliers", 1e-4)
     # C5 with the sparse-embedding stress of Sec. 3.2.2: per step, 90 % of the rows of the
     # embedding matrix (the first tensor) receive no gradient at all
     if name == "c5_sparse_embed":

@@ -418,6 +418,74 @@ def test_step_can_be_captured_in_a_hip_graph(so, gpu):
             assert torch.equal(got, ref)
 
 
+# --------------------------- blocks of 2048 elements (the large-block setting of Sec. 4.2)
+
+@pytest.mark.parametrize("bm", (2, 3, 4))
+@pytest.mark.parametrize("bv", (2, 3, 4))
+def test_block_2048_all_formats(so, gpu, bm, bv):
+    """One workgroup per block: maxima across four wavefronts, the quantile (rank 205 of 2048) by
+    radix select.  Every format, both gradient types and codebooks, full blocks and a ragged end."""
+    for bf16, n, de in ((False, 5 * 2048 + 777, False), (True, 3 * 2048, True), (True, 11 * 2048 + 1283, False)):
+        run_teacher_forced(so, gpu, n, bm, bv, 2048, bf16=bf16, steps=3, seed0=40 + 7 * bm + bv, de=de,
+                           std=1e-4 if bf16 else 1e-3, kind="normal_outliers" if bf16 else "student_t3")
+
+
+@pytest.mark.parametrize("n", (1, 7, 8, 511, 512, 513, 1023, 2047, 2048, 2049, 2560, 4095, 4097, 6143, 20481))
+def test_block_2048_ragged_sizes(so, gpu, n):
+    run_free(so, gpu, n, 2, 3, 2048, bf16=True, steps=3, std=1e-4, seed0=n)
+    run_free(so, gpu, n, 3, 4, 2048, steps=3, seed0=n + 1)
+
+
+def test_block_2048_quantile_settings_variants_and_degenerate_blocks(so, gpu):
+    n = 9 * 2048 + 300
+    for p in (0.0, 0.02, 0.3, 0.5, 0.95):
+        run_teacher_forced(so, gpu, n, 4, 2, 2048, steps=3, p=p, seed0=int(p * 100))
+        run_teacher_forced(so, gpu, n, 2, 3, 2048, steps=3, p=p, seed0=int(p * 100) + 1, bf16=True, std=1e-4)
+    run_teacher_forced(so, gpu, n, 3, 3, 2048, steps=4, stochastic=0, seed0=77)
+    for optimizer in ("adam_l2", "adabelief"):
+        kw = dict(optimizer=optimizer, grad_scale=1.0 / 1024, wd=0.1, bf16_copy=True,
+                  eps=1e-12 if optimizer == "adabelief" else 1e-8, std=1.024)
+        run_teacher_forced(so, gpu, n, 2, 3, 2048, True, steps=3, **kw)
+        run_free(so, gpu, n, 4, 2, 2048, True, steps=6, de=True, **kw)
+    run_teacher_forced(so, gpu, 6000, 2, 3, 2048, steps=3, off=8 * (1 << 33) + 2560 * 7, seed=123456789)
+    # constant blocks (every key equal: the radix select walks one bin per pass), zero blocks, sparse blocks
+    from paper_2505_00347_amd import synth
+    B = 2048
+    nn = 12 * B + 11
+    oc, gc = make_cfgs(so, gpu, 2, 3, B, True)
+    p = synth.make_params(nn)
+    st = so.State(nn, oc)
+    side = GpuSide(gpu, nn, gc)
+    for step in range(1, 7):
+        g = special_grads(nn, B, step) if step != 4 else np.zeros(nn, np.float32)
+        bits, g = synth.round_to_bf16(g)
+        side.load(p, st)
+        side.step(dev(bits), step)
+        margin = so.step_packed(p, g, st, step, oc, want_margin=True)
+        compare_step(so, oc, nn, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
+
+
+def test_block_2048_config5_shape_ten_steps(so, gpu):
+    """The metric's format with blocks of 2048 on a LLaMA-7B-shaped slice: ten teacher-forced and
+    ten free-running steps."""
+    run_teacher_forced(so, gpu, 4096 * 512, 2, 3, 2048, bf16=True, steps=10, kind="normal_outliers", std=1e-4, seed0=8000)
+    flips, tainted = run_free(so, gpu, 4096 * 512 + 4096, 2, 3, 2048, bf16=True, steps=10, kind="normal_outliers",
+                              std=1e-4, seed0=8100)
+    note(f"block 2048, config-5 format, 2.1 M elements x 10 free-running steps: {flips} flips, {tainted} blocks diverged")
+
+
+def test_block_2048_is_a_flat_buffer_format(gpu):
+    """The multi-tensor launch has no kernels for blocks of 2048."""
+    import ctypes as C
+    solo = gpu
+    cfg = solo.make_config(bits_m=2, bits_v=3, block_size=2048)
+    arr = (solo.solo_tensor * 1)()
+    assert solo.solo_multi_units(arr, 1, cfg) == 0
+    buf = (C.c_uint8 * 256)()
+    assert solo.solo_multi_table_build(arr, 1, cfg, buf, 256, check=False)[0] == solo.SOLO_E_UNSUPPORTED
+    assert solo.solo_adamw_step_multi(16, 1, 1, 0, None, 1, cfg, check=False) == solo.SOLO_E_UNSUPPORTED
+
+
 # ------------------------------------------------------- many tensors in one launch
 
 @pytest.mark.parametrize("bm,bv,B,bf16,de,optimizer,extras", [(2, 3, 128, True, False, "adamw", False),
