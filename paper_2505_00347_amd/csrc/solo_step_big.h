@@ -10,11 +10,11 @@
 //     across the rows, four words of LDS and one barrier across the wavefronts;
 //   * the p-quantile is the rank-205 element of 2048 values (p = 0.1), far too deep for rounds
 //     of "extract the minimum".  It is found by a radix select on the bit patterns (non-negative
-//     floats order like their bits): three passes over 11 + 11 + 9 bits, each a histogram of the
-//     keys that still match the selected prefix (LDS atomics), a prefix sum of the 256 threads'
-//     partial counts (DPP scan per wavefront, four totals through LDS) and the thread whose
-//     bins hold the rank announcing digit and remaining rank.  After the third pass the prefix
-//     is the order statistic itself, multiplicities included, exactly.
+//     floats order like their bits): three passes over 11 + 10 + 10 bits, each a histogram of the
+//     keys that still match the selected prefix (LDS atomics), one barrier, and two prefix sums
+//     (DPP scans) that every wavefront runs for itself to find the bin that holds the rank.
+//     After the third pass the prefix is the order statistic itself, multiplicities included,
+//     exactly.  Four barriers per block in all.
 //   * the base alpha, the division and the level tables are computed by every wavefront (every
 //     16 lanes) for itself: cheaper than another barrier.
 // One workgroup per block, every wavefront stages and writes back the words of its own 512
@@ -29,16 +29,21 @@ constexpr int kBigBlock = 2048;
 constexpr int kBigWaves = kBigBlock / kIter;      // 4 wavefronts, one workgroup per block
 static_assert(kBigWaves == 4, "one workgroup of four wavefronts per block");
 
-// LDS of one wavefront (32-bit words).
+// LDS of a workgroup (32-bit words).  `work` first serves the four wavefronts as the staging
+// areas of their layout transpositions (64 x 12 words each), then, behind the barrier of the block
+// maxima, the whole workgroup as the histograms of the selection.  A histogram keeps 4 pad words
+// after the 32 (16) bins that one lane sums, so that the lanes' 128-bit reads spread over the banks.
 struct BigLayout {
-    static constexpr int kOffStage = 0;                       // 64 x 12: staging of the layout transposition
-    static constexpr int kOffImgM = 64 * kColStride;          // the wavefront's words of each code stream (<= 64, + 1)
-    static constexpr int kOffImgV = kOffImgM + 68;
-    static constexpr int kOffTv = ((kOffImgV + 68 + 15) / 16) * 16;   // level tables, 64-byte aligned
-    static constexpr int kOffTm = kOffTv + 16;
-    static constexpr int kSlab = kOffTm + 16;
+    static constexpr int kStage = 64 * kColStride;            // per wavefront
+    static constexpr int kHist0 = 0, kHist1 = 2048 + 4 * 64, kHist2 = kHist1 + 1024 + 4 * 64;
+    static constexpr int kWork = kHist2 + 1024 + 4 * 64;      // 4864 words
+    static constexpr int kOffImgM = 0;                        // per wavefront: its words of each code stream (<= 64, + 1)
+    static constexpr int kOffImgV = 68;
+    static constexpr int kOffTv = 144;                        // level tables, 64-byte aligned
+    static constexpr int kOffTm = 160;
+    static constexpr int kSlab = 176;
 };
-constexpr int kBigHist = 2048;                                // bins of the widest radix pass
+static_assert(BigLayout::kWork >= kBigWaves * BigLayout::kStage, "the staging areas lie inside the work area");
 
 // Maximum over the 64 lanes of a wavefront (uniform result).
 __device__ __forceinline__ uint32_t wave_max(uint32_t x)
@@ -64,51 +69,48 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x)
 
 // The rank-th smallest (1-based, uniform over the workgroup) of the 8 keys that each of the 256
 // threads holds: bit patterns of non-negative floats, +inf for absent elements (the rank never
-// reaches those).  hist: kBigHist words, xch: 8 words, both shared by the workgroup.
-__device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[8], uint32_t rank, uint32_t tid, uint32_t lane,
-                                                uint32_t wave, uint32_t *hist, uint32_t *xch)
+// reaches those).  Radix select over 11 + 10 + 10 bits.  A pass: every thread adds its keys that
+// still match the selected prefix to the pass's histogram (in `work`, zeroed before
+// the workgroup's previous barrier), one barrier, and then every wavefront finds the bin of the
+// rank for itself: a lane sums 32 (16) consecutive bins, a prefix sum over the wavefront names
+// the lane whose bins hold the rank, and a second prefix sum over that lane's bins, one per
+// lane, names the bin.  No exchange between the wavefronts beyond the histogram.
+__device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[8], uint32_t rank, uint32_t lane, uint32_t *work)
 {
     uint32_t prefix = 0;                          // the bits selected so far (bit 31 of a key is 0)
 #pragma unroll
     for (int pass = 0; pass < 3; ++pass) {
-        constexpr int kBits[3] = {11, 11, 9}, kShift[3] = {20, 9, 0};
+        constexpr int kBits[3] = {11, 10, 10}, kShift[3] = {20, 10, 0};
+        constexpr int kOff[3] = {BigLayout::kHist0, BigLayout::kHist1, BigLayout::kHist2};
         const int bits = kBits[pass], sh = kShift[pass];
-        const uint32_t bins = 1u << bits, per = bins / 256u;        // 8, 8, 2 bins per thread
-        for (uint32_t i = tid; i < bins / 4u; i += 256u) reinterpret_cast<uint4 *>(hist)[i] = make_uint4(0, 0, 0, 0);
-        __syncthreads();
+        const uint32_t bins = 1u << bits, per = bins / 64u;          // 32, 16, 16 bins per lane
+        const int lper = bits - 6;                                   // log2(per)
+        uint32_t *const h = work + kOff[pass];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const bool match = pass == 0 || (key[j] >> (sh + bits)) == prefix;
-            if (match) atomicAdd(&hist[(key[j] >> sh) & (bins - 1u)], 1u);
+            const uint32_t b = (key[j] >> sh) & (bins - 1u);
+            if (match) atomicAdd(&h[b + ((b >> lper) << 2)], 1u);
         }
         __syncthreads();
-        uint32_t c[8], s = 0;
+        uint32_t s = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            c[i] = (uint32_t)i < per ? hist[tid * per + (uint32_t)i] : 0u;
-            s += c[i];
+            if ((uint32_t)(4 * i) < per) {
+                const uint4 c4 = reinterpret_cast<const uint4 *>(h)[lane * (per / 4u + 1u) + (uint32_t)i];
+                s += (c4.x + c4.y) + (c4.z + c4.w);
+            }
         }
         const uint32_t incl = wave_inclusive_sum(s);
-        if (lane == 63u) xch[wave] = incl;
-        __syncthreads();
-        uint32_t below = incl - s;                                   // keys in the bins of the threads before this one
-#pragma unroll
-        for (int w = 0; w < kBigWaves - 1; ++w) below += (uint32_t)w < wave ? xch[w] : 0u;
-        if (below < rank && rank <= below + s) {                     // exactly one thread
-            uint32_t acc = below, digit = 0, left = 0;
-            bool found = false;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (!found && (uint32_t)i < per) {
-                    if (rank <= acc + c[i]) { digit = tid * per + (uint32_t)i; left = rank - acc; found = true; }
-                    else acc += c[i];
-                }
-            }
-            xch[4] = digit; xch[5] = left;
-        }
-        __syncthreads();
-        prefix = (prefix << bits) | xch[4];
-        rank = xch[5];
+        const uint64_t holder = __builtin_amdgcn_ballot_w64(incl - s < rank && rank <= incl);   // one lane
+        const uint32_t sel = (uint32_t)__builtin_ctzll(holder | (1ull << 63));
+        rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl - s), (int)sel);
+        const uint32_t c = lane < per ? h[sel * (per + 4u) + lane] : 0u;
+        const uint32_t incl2 = wave_inclusive_sum(c);
+        const uint64_t holder2 = __builtin_amdgcn_ballot_w64(incl2 - c < rank && rank <= incl2);
+        const uint32_t sel2 = (uint32_t)__builtin_ctzll(holder2 | (1ull << 63));
+        rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl2 - c), (int)sel2);
+        prefix = (prefix << bits) | (sel * per + sel2);
     }
     return prefix;
 }
@@ -117,7 +119,7 @@ __device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[8], uint32
 // with bounds checks on every element), executed by the four wavefronts of the calling workgroup.
 template <int BM, int BV, bool BF16, bool MDE, bool TAIL, bool EXT>
 __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t blk, const uint32_t lane,
-                                               const uint32_t wave, uint32_t *const slab, uint32_t *const hist,
+                                               const uint32_t wave, uint32_t *const slab, uint32_t *const work,
                                                uint32_t *const xch, const uint32_t *const lds_de)
 {
     constexpr int L = (1 << (BM - 1)) - 1;
@@ -140,7 +142,7 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     // ---- loads: parameters and gradients, the wavefront's code words, the block's scalars
     RawPG raw = load_pg<BF16, TAIL>(a, ew0, lane);
     const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;
-    float4 *const stage = reinterpret_cast<float4 *>(slab + BigLayout::kOffStage);
+    float4 *const stage = reinterpret_cast<float4 *>(work + wave * BigLayout::kStage);
     float4 *const st_c = stage + (lane + lane / 8u);
     float4 *const st_l = stage + (2u * lane + lane / 4u);
     // words of the wavefront's 512 elements: the first may start inside a word (ten-to-a-word codes)
@@ -266,6 +268,18 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
         for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
     }
 
+    // ---- the work area becomes the histograms of the selection: a wavefront clears its own staging
+    // area (it is done with it; the others may still be using theirs) and its share of the rest
+    {
+        uint4 *const own = reinterpret_cast<uint4 *>(work + wave * BigLayout::kStage);
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < BigLayout::kStage / 4 / 64; ++i) own[lane + 64u * (uint32_t)i] = make_uint4(0, 0, 0, 0);
+        constexpr int kRest = (BigLayout::kWork - kBigWaves * BigLayout::kStage) / 4;    // 128-bit words behind the staging areas
+        uint4 *const rest = reinterpret_cast<uint4 *>(work + kBigWaves * BigLayout::kStage);
+        for (uint32_t i = tid; i < (uint32_t)kRest; i += kBigWaves * 64) rest[i] = make_uint4(0, 0, 0, 0);
+    }
+
     // ---- block maxima over the four wavefronts
     {
         const uint32_t wm_max = wave_max(f2u(m_absmax)), wv_max = wave_max(f2u(v_max));
@@ -276,7 +290,6 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     float dv = u2f(umax(umax(xch[4], xch[5]), umax(xch[6], xch[7])));
     if (dm < kTiny) dm = 0.0f;
     if (dv < kTiny) dv = 0.0f;
-    // (the selection writes the exchange words only behind its own first two barriers)
 
     // ---- the r-th smallest v^ of the block
     uint32_t rank = a.rank_full;
@@ -288,7 +301,7 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     uint32_t key[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) key[j] = (TAIL && !ok[j]) ? kInfBits : f2u(vh[j]);
-    const uint32_t xp_bits = select_rank(key, rank, tid, lane, wave, hist, xch);
+    const uint32_t xp_bits = select_rank(key, rank, lane, work);
 
     // ---- encoder constants (every 16 lanes for themselves), codes, the wavefront's words
     const uint32_t lig = lane & 15u, gshift = lane & 16u;
@@ -327,8 +340,8 @@ __global__ __launch_bounds__(kBigWaves * 64, SOLO_MIN_WAVES)
 void big_kernel(const StepArgs a)
 {
     constexpr int kDeWords = (MDE && BM >= 3) ? 4 * DeBuckets<BM>::N : 16;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_work[BigLayout::kWork];
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kBigWaves * BigLayout::kSlab];
-    __shared__ __attribute__((aligned(64))) uint32_t lds_hist[kBigHist];
     __shared__ __attribute__((aligned(64))) uint32_t lds_xch[8];
     __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
     load_de_table<BM, MDE, kDeWords>(lds_de);
@@ -337,9 +350,9 @@ void big_kernel(const StepArgs a)
     const uint64_t blk = blockIdx.x;
     uint32_t *const slab = lds_slab + wave * BigLayout::kSlab;
     if ((blk + 1) * kBigBlock <= a.n)
-        step_block_big<BM, BV, BF16, MDE, false, EXT>(a, blk, lane, wave, slab, lds_hist, lds_xch, lds_de);
+        step_block_big<BM, BV, BF16, MDE, false, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
     else
-        step_block_big<BM, BV, BF16, MDE, true, EXT>(a, blk, lane, wave, slab, lds_hist, lds_xch, lds_de);
+        step_block_big<BM, BV, BF16, MDE, true, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
 }
 
 template <int BM, bool MDE>
