@@ -185,8 +185,8 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
  * index_offset = cfg->index_offset + sum over the tensors before it of n rounded up to a multiple
  * of 2560, so its result is that of solo_adamw_step_mp on the tensor alone with that
  * index_offset.  The table depends on the pointers, the sizes, cfg's state format (code widths,
- * block size, codebook) and index_offset; it need not be rebuilt when only scalars of cfg or the
- * step change. */
+ * block size, codebook), grad_dtype and index_offset; it need not be rebuilt when only scalars of
+ * cfg or the step change. */
 typedef struct solo_tensor {
     float *param;          /* fp32[n], read and written                      */
     void *param_bf16;      /* bf16[n] or NULL: bf16 copy of the new parameters */
@@ -199,11 +199,12 @@ typedef struct solo_tensor {
     uint64_t n;            /* elements                                       */
 } solo_tensor;
 
-/* Number of work units the tensors are cut into for cfg's state format (a unit is the 2560 or
- * 5120 elements one wavefront of that format's kernel owns; the ragged end of a tensor counts
- * one unit per 512 elements, each a wavefront of its own); 0 if cfg is invalid.  At most 2^24
- * tensors per table.  Block sizes 64 and 128 only (0 for 2048; the table build and the step
- * return SOLO_E_UNSUPPORTED). */
+/* Number of work units the tensors are cut into for cfg's state format and gradient type (a unit
+ * is the 2560 or 5120 elements one wavefront of that format's kernel owns, the ragged end of a
+ * tensor counts one unit per 512 elements; with fp32 gradients and the linear codebook a unit is
+ * 2560 elements or a tensor's shorter end, shared by five wavefronts); 0 if cfg is invalid.  At
+ * most 2^24 tensors per table.  Block sizes 64 and 128 only (0 for 2048; the table build and the
+ * step return SOLO_E_UNSUPPORTED). */
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg);
 
 /* Bytes of the table for `count` tensors and `units` units. */

@@ -265,9 +265,13 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg)
 {
     if (!tensors || !solo::config_ok(cfg) || cfg->block_size == solo::kLargeBlock) return 0;
-    const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
-                                                     (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
+    const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
     uint64_t units = 0;
+    if (solo::multi_chunked(cfg->grad_dtype == SOLO_GRAD_BF16, mde)) {
+        for (uint32_t k = 0; k < count; ++k) units += (tensors[k].n + solo::kTileUnit - 1) / solo::kTileUnit;
+        return units;
+    }
+    const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size, mde);
     for (uint32_t k = 0; k < count; ++k) units += solo::multi_full_units(tensors[k].n, unit) + solo::multi_ragged_chunks(tensors[k].n, unit);
     return units;
 }
@@ -288,6 +292,8 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
     if (units > (1ull << 31)) return SOLO_E_UNSUPPORTED;
     const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
                                                      (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
+    const bool chunked = solo::multi_chunked(cfg->grad_dtype == SOLO_GRAD_BF16,
+                                             (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
     solo::TensorEntry *entries = static_cast<solo::TensorEntry *>(table_host);
     uint32_t *map = reinterpret_cast<uint32_t *>(static_cast<char *>(table_host) + solo::multi_map_offset(count));
     uint64_t unit0 = 0, xi_offset = cfg->index_offset;
@@ -309,7 +315,9 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
         e.index_offset = xi_offset;
         e.reserved = 0;
         // full units first, then the 512-element iterations of the ragged end, one entry each
-        const uint64_t nf = solo::multi_full_units(t.n, unit), nc = solo::multi_ragged_chunks(t.n, unit);
+        // (chunked formats: one entry per 2560-element unit, the shorter last one included)
+        const uint64_t nf = chunked ? (t.n + solo::kTileUnit - 1) / solo::kTileUnit : solo::multi_full_units(t.n, unit);
+        const uint64_t nc = chunked ? 0 : solo::multi_ragged_chunks(t.n, unit);
         for (uint64_t u = 0; u < nf; ++u) map[unit0 + u] = k;
         for (uint64_t c = 0; c < nc; ++c) map[unit0 + nf + c] = k | ((uint32_t)c << solo::kMapChunkShift) | solo::kMapRagged;
         unit0 += nf + nc;
@@ -336,9 +344,11 @@ int solo_adamw_step_multi(const void *table_device, uint32_t count, uint64_t uni
                                                      solo::multi_map_offset(count));
     ma.total_units = units;
     ma.any_bf16_copy = (table_flags & SOLO_TABLE_BF16_COPY) ? 1u : 0u;
-    ma.groups_per_xcd = ((units + solo::kWaves - 1) / solo::kWaves + solo::kXcds - 1) / solo::kXcds;
     const bool bf16 = cfg->grad_dtype == SOLO_GRAD_BF16;
     const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
+    // wavefronts of the launch: one per unit, or five per 2560-element unit of a chunked format
+    const uint64_t slots = solo::multi_chunked(bf16, mde) ? units * (solo::kTileUnit / solo::kIter) : units;
+    ma.groups_per_xcd = ((slots + solo::kWaves - 1) / solo::kWaves + solo::kXcds - 1) / solo::kXcds;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (cfg->bits_m) {

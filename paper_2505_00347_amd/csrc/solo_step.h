@@ -597,6 +597,15 @@ inline int unit_elems(uint32_t bits_m, uint32_t bits_v, uint32_t block_size, boo
     return 0;
 }
 
+// The formats whose flat buffers run one wavefront per 512-element iteration at every size do so
+// in a multi-tensor launch as well: their tables hold one entry per 2560-element unit (a tensor's
+// shorter end included), and five wavefronts share a unit.
+inline bool multi_chunked(bool bf16, bool mde)
+{
+    return bf16 ? chunked_up_to<128, true, false>() == ~0ull
+                : (mde ? chunked_up_to<128, false, true>() == ~0ull : chunked_up_to<128, false, false>() == ~0ull);
+}
+
 // ---- pieces shared by the two tile functions
 
 // Stages a full super-tile's state in LDS (coalesced, 16 bytes per lane): every load is issued
@@ -1590,6 +1599,40 @@ void multi_kernel(const MultiArgs ma)
     }
 }
 
+// The multi-tensor step of the formats that always run one wavefront per 512-element iteration:
+// a map entry stands for a 2560-element unit of its tensor (the last one of a tensor may be
+// shorter), five consecutive wavefronts take its five iterations.
+template <int BM, int BV, int B, bool BF16, bool MDE, bool EXT>
+__global__ __launch_bounds__(kWaves * 64, SOLO_MIN_WAVES)
+void multi_chunk_kernel(const MultiArgs ma)
+{
+    constexpr int kChunks = kTileUnit / kIter;
+    using Lay = SlabLayout<BM, BV, B, MDE, kTileUnit, 8>;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWaves * Lay::kSlab];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[Lay::kDeWords];
+    load_de_table<BM, MDE, Lay::kDeWords>(lds_de);
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint64_t slot = (uint64_t)blockIdx.x * kWaves + wave;
+    const uint64_t unit = slot / kChunks;
+    const int chunk = (int)(slot % kChunks);
+    if (unit >= ma.total_units) return;
+    const uint32_t me = ma.unit_map[unit];                      // uniform: scalar loads
+    const TensorEntry &e = ma.entries[me & kMapTensorMask];
+    StepArgs a = ma.common;
+    a.param = e.param; a.param_bf16 = e.param_bf16; a.grad = e.grad;
+    a.m_words = e.m_words; a.m_scale = e.m_scale;
+    a.v_words = e.v_words; a.v_scale = e.v_scale; a.v_base = e.v_base;
+    a.n = e.n; a.index_offset = e.index_offset;
+    uint32_t *const slab = lds_slab + wave * Lay::kSlab;
+    const uint64_t tile = unit - e.unit0;
+    if ((tile + 1) * kTileUnit <= a.n)
+        step_tile<BM, BV, B, BF16, MDE, false, EXT, kTileUnit, true>(a, tile, lane, slab, lds_de, chunk);
+    else if (tile * kTileUnit + (uint64_t)chunk * kIter < (a.n + 79) / 80 * 80)   // up to the end of the last code word
+        step_tile<BM, BV, B, BF16, MDE, true, true, kTileUnit>(a, tile, lane, slab, lds_de, chunk);
+}
+
 // Host-side launcher of one instantiation family (fixed bits_m and 1st-moment codebook);
 // defined in solo_step_m{2,3,4}{,_de}.hip so that the families compile in parallel.
 template <int BM, bool MDE>
@@ -1646,9 +1689,16 @@ hipError_t launch_multi_impl(uint32_t bits_v, uint32_t block_size, bool bf16, co
     if (grid == 0 || grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const StepArgs &c = args.common;
     const bool ext = args.any_bf16_copy || c.grad_scale || c.belief || c.l2 != 0.0f;
+    const bool chunked = multi_chunked(bf16, MDE);
 #define SOLO_LAUNCH(BV_, B_, BF_, EXT_)                                                                 \
-    hipLaunchKernelGGL((multi_kernel<BM, BV_, B_, BF_, MDE, EXT_>), dim3((uint32_t)grid),               \
-                       dim3(kWaves * 64), 0, stream, args)
+    do {                                                                                                \
+        if (chunked)                                                                                    \
+            hipLaunchKernelGGL((multi_chunk_kernel<BM, BV_, B_, BF_, MDE, EXT_>), dim3((uint32_t)grid), \
+                               dim3(kWaves * 64), 0, stream, args);                                     \
+        else                                                                                            \
+            hipLaunchKernelGGL((multi_kernel<BM, BV_, B_, BF_, MDE, EXT_>), dim3((uint32_t)grid),       \
+                               dim3(kWaves * 64), 0, stream, args);                                     \
+    } while (0)
 #define SOLO_CASE(BV_, B_)                                                                              \
     if (bits_v == BV_ && block_size == B_) {                                                            \
         if (bf16) { if (ext) SOLO_LAUNCH(BV_, B_, true, true); else SOLO_LAUNCH(BV_, B_, true, false); } \

@@ -542,7 +542,7 @@ def test_multi_tensor_table_rejects_bad_descriptors(gpu):
     import ctypes as C
     import torch
     solo = gpu
-    cfg = solo.make_config(bits_m=2, bits_v=3)
+    cfg = solo.make_config(bits_m=2, bits_v=3, flags=solo.SOLO_FLAG_STOCHASTIC | solo.SOLO_FLAG_M_DYNAMIC_EXPONENT)
     n = 3000
     st = solo.SoloState(n, cfg)
     p = torch.zeros(n, device="cuda")
@@ -552,6 +552,8 @@ def test_multi_tensor_table_rejects_bad_descriptors(gpu):
                               st.v_codes.data_ptr(), st.v_scale.data_ptr(), st.v_base.data_ptr(), n)
     units = solo.solo_multi_units(arr, 1, cfg)
     assert units == 6                            # 3000 elements, all of them a ragged end: one unit per 512 elements
+    # fp32 gradients with the linear codebook: units of 2560 elements, the shorter end included
+    assert solo.solo_multi_units(arr, 1, solo.make_config(bits_m=2, bits_v=3)) == 2
     nbytes = solo.solo_multi_table_bytes(1, units)
     assert nbytes == 96 + 4 * units
     buf = (C.c_uint8 * nbytes)()
