@@ -183,6 +183,11 @@ def main():
                     help="which of the allocations the timed steps run on: the one whose warm-up "
                          "time is the median of all (the default: what a caller gets on a typical "
                          "allocation), the fastest, or the first")
+    ap.add_argument("--state-apart", action="store_true",
+                    help="allocate the packed state behind a spacer that ends 96 GiB after the start of "
+                         "the parameters (freed again at once): in a process that starts on an idle "
+                         "GPU the state then lies in another third of HBM than the parameters "
+                         "(see paper_2505_00347_amd/hbm_regions.py)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
@@ -226,6 +231,12 @@ def main():
                 self.extras = {"param_bf16": torch.empty(n, dtype=torch.bfloat16, device="cuda"),
                                "grad_scale": torch.tensor([0.5], dtype=torch.float32, device="cuda")}
             self.step = 0
+            spacer = None
+            if args.state_apart:
+                used = 4 * n + 2 * (2 if w.grad_dtype == "bf16" else 4) * n + (4 * n if mp else 0)
+                room = torch.cuda.mem_get_info()[0] - (8 << 30)
+                if 0 < (96 << 30) - used < room:
+                    spacer = torch.empty((96 << 30) - used, dtype=torch.uint8, device="cuda")
             if args.launch == "flat":
                 self.state = solo.SoloState(n, cfg)
             else:
@@ -241,6 +252,7 @@ def main():
                 if args.launch == "multi":
                     self.tables = [solo.SoloMultiTable([(t[0], t[1][k], t[2], t[3]) for t in self.tensors], cfg)
                                    for k in (0, 1)]
+            del spacer
             torch.cuda.synchronize()
 
         def one_step(self):
@@ -327,7 +339,7 @@ def main():
                      "stream_probe": probe},
         # the warm-up time of every allocation that was tried, which one the timed steps ran on, and
         # the roofline fraction the warm-up steps gave on the first and on the fastest of them
-        "placement": {"policy": args.placement_policy if len(trial_ms) > 1 else "first",
+        "placement": {"policy": (args.placement_policy if len(trial_ms) > 1 else "first") + (", state apart" if args.state_apart else ""),
                       "candidates_ms": trial_ms, "chosen": chosen,
                       "frac_first": frac_of(trial_ms[0]), "frac_best": frac_of(trial_ms[order[0]]),
                       "frac_median": frac_of(trial_ms[order[(len(order) - 1) // 2]])},
