@@ -183,11 +183,14 @@ def main():
                     help="which of the allocations the timed steps run on: the one whose warm-up "
                          "time is the median of all (the default: what a caller gets on a typical "
                          "allocation), the fastest, or the first")
-    ap.add_argument("--state-apart", action="store_true",
-                    help="allocate the packed state behind a spacer that ends 96 GiB after the start of "
-                         "the parameters (freed again at once): in a process that starts on an idle "
-                         "GPU the state then lies in another third of HBM than the parameters "
-                         "(see paper_2505_00347_amd/hbm_regions.py)")
+    ap.add_argument("--no-state-apart", dest="state_apart", action="store_false",
+                    help="allocate parameters, gradients and state one behind the other.  By default the "
+                         "packed state is allocated behind a spacer that ends 96 GiB after the start of "
+                         "the parameters (freed again at once), the library's allocation rule for "
+                         "MI355X: the state must not share a third of HBM with the parameters (see "
+                         "include/solo.h and paper_2505_00347_amd/hbm_regions.py).  With more than one "
+                         "placement the first allocation is made without the spacer and reported as "
+                         "frac_first")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the step is block-local and this build has no "
@@ -222,7 +225,7 @@ def main():
         """One set of device buffers of the workload (parameters, two gradient buffers that the
         steps alternate between, the packed state), and the steps run on it so far."""
 
-        def __init__(self):
+        def __init__(self, apart=False):
             self.p = device_params(torch, w, synth.SEED_PARAM)
             self.grads = [device_grads(torch, n, w.grad_kind, w.grad_std,
                                        synth.seed_grad(w.config_id, k), gdtype, sparse_rows_of(w)) for k in (1, 2)]
@@ -232,8 +235,8 @@ def main():
                                "grad_scale": torch.tensor([0.5], dtype=torch.float32, device="cuda")}
             self.step = 0
             spacer = None
-            if args.state_apart:
-                used = 4 * n + 2 * (2 if w.grad_dtype == "bf16" else 4) * n + (4 * n if mp else 0)
+            if apart and n >= (1 << 28):         # (smaller buffers run the kernels that show no such effect)
+                used = 4 * n + 2 * (2 if w.grad_dtype == "bf16" else 4) * n + (2 * n if mp else 0)
                 room = torch.cuda.mem_get_info()[0] - (8 << 30)
                 if 0 < (96 << 30) - used < room:
                     spacer = torch.empty((96 << 30) - used, dtype=torch.uint8, device="cuda")
@@ -252,7 +255,9 @@ def main():
                 if args.launch == "multi":
                     self.tables = [solo.SoloMultiTable([(t[0], t[1][k], t[2], t[3]) for t in self.tensors], cfg)
                                    for k in (0, 1)]
-            del spacer
+            if spacer is not None:
+                del spacer
+                torch.cuda.empty_cache()         # the spacer goes back to the driver, not into torch's cache
             torch.cuda.synchronize()
 
         def one_step(self):
@@ -279,19 +284,29 @@ def main():
             return [s.elapsed_time(e) for s, e in zip(starts, ends)]
 
     # Where the buffers land in physical HBM changes the rate this machine delivers for identical code
-    # by several percent.  The workload is therefore allocated up to --placements times (every
-    # candidate held until the choice is made), each allocation is warmed up and timed, and the
-    # timed steps run on the allocation whose time is the median of the candidates (policy
-    # "median", the headline: a typical allocation); the times of all candidates, and the
-    # roofline fractions of the first and of the fastest, are reported beside it.
+    # by 8 %: the step is slower when the code words of the state lie in the same third of HBM
+    # (96 GiB) as the parameters.  The candidates are therefore allocated by the library's rule
+    # (state apart, see --no-state-apart).  What a caller who allocates everything one behind the
+    # other gets is measured first, on an allocation of its own, and reported as frac_first.
+    # Up to --placements candidates are allocated (every one held until the choice is made), each
+    # is warmed up and timed, and the timed steps run on the one whose time is the median of the
+    # candidates (policy "median", the headline: a typical allocation); the times of all candidates,
+    # and the roofline fractions of the first and of the fastest, are reported beside it.
     cands, trial_ms = [], []
     trials = max(args.warmup, 2) if args.placements > 1 else args.warmup
+    naive_ms = None
+    if args.state_apart and args.placements > 1:
+        r = Resident(apart=False)
+        ms = r.run(trials)
+        naive_ms = sorted(ms[-2:])[0] if ms else None
+        del r
+        torch.cuda.empty_cache()
     for k in range(max(1, args.placements)):
         if k:                                    # every candidate stays allocated until the choice is made
             free_b, total_b = torch.cuda.mem_get_info()
             if free_b < (total_b - free_b) / k + (8 << 30):
                 break
-        r = Resident()
+        r = Resident(apart=args.state_apart)
         ms = r.run(trials)
         cands.append(r)
         trial_ms.append(sorted(ms[-2:])[0] if ms else None)
@@ -339,9 +354,12 @@ def main():
                      "stream_probe": probe},
         # the warm-up time of every allocation that was tried, which one the timed steps ran on, and
         # the roofline fraction the warm-up steps gave on the first and on the fastest of them
-        "placement": {"policy": (args.placement_policy if len(trial_ms) > 1 else "first") + (", state apart" if args.state_apart else ""),
+        "placement": {"policy": (args.placement_policy if len(trial_ms) > 1 else "first")
+                      + (", state apart" if args.state_apart else ", buffers one behind the other"),
                       "candidates_ms": trial_ms, "chosen": chosen,
-                      "frac_first": frac_of(trial_ms[0]), "frac_best": frac_of(trial_ms[order[0]]),
+                      "first_ms": naive_ms if naive_ms is not None else trial_ms[0],
+                      "frac_first": frac_of(naive_ms if naive_ms is not None else trial_ms[0]),
+                      "frac_best": frac_of(trial_ms[order[0]]),
                       "frac_median": frac_of(trial_ms[order[(len(order) - 1) // 2]])},
     }
     del res, p

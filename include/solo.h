@@ -148,7 +148,7 @@ int solo_state_init(uint32_t *m_codes, float *m_scale,
  * not matter.  A process that starts on an idle GPU receives physical memory in allocation order:
  * a long-lived optimizer does well to allocate its state so that it does not end up in the
  * third of HBM that holds the parameters (python -m paper_2505_00347_amd.hbm_regions measures
- * the effect; bench.py --state-apart shows one way to do it). */
+ * the effect; bench.py shows one way to do it). */
 int solo_adamw_step(float *param, const void *grad,
                     uint32_t *m_codes, float *m_scale,
                     uint32_t *v_codes, float *v_scale, float *v_base,
