@@ -152,6 +152,36 @@ def test_multi_tensor_table_layout(solo):
     assert solo.solo_multi_units(arr, len(sizes), solo.make_config(2, 3, 100, 1)) == 0
 
 
+def test_multi_table_of_a_chunked_format_and_large_blocks(solo):
+    """With fp32 gradients and the linear codebook a table holds one entry per 2560-element unit
+    (the shorter end of a tensor included); blocks of 2048 elements have no multi-tensor launch
+    but all size queries."""
+    import numpy as np
+    cfg = solo.make_config(bits_m=2, bits_v=2, block_size=64, grad_dtype=solo.SOLO_GRAD_FP32)
+    sizes = [1, 2559, 2560, 2561, 0, 7680, 12801]
+    arr = (solo.solo_tensor * len(sizes))()
+    for k, n in enumerate(sizes):
+        base = 0x10000000 * (k + 1)
+        arr[k] = solo.solo_tensor(base, None, *[base + 0x1000000 * j for j in range(2, 8)], n)
+    want_units = [-(-n // 2560) for n in sizes]
+    units = solo.solo_multi_units(arr, len(sizes), cfg)
+    assert units == sum(want_units)
+    nbytes = solo.solo_multi_table_bytes(len(sizes), units)
+    buf = np.zeros(nbytes, np.uint8)
+    rc, flags = solo.solo_multi_table_build(arr, len(sizes), cfg, buf.ctypes.data, nbytes)
+    assert rc == solo.SOLO_OK and flags == 0
+    unit_map = buf[96 * len(sizes):].view(np.uint32)
+    assert list(unit_map) == [k for k, u in enumerate(want_units) for _ in range(u)]
+    # the same tensors with bf16 gradients: super-tiles plus one entry per 512 elements of a ragged end
+    cfg16 = solo.make_config(bits_m=2, bits_v=2, block_size=64, grad_dtype=solo.SOLO_GRAD_BF16)
+    assert solo.solo_multi_units(arr, len(sizes), cfg16) != units
+    big = solo.make_config(bits_m=2, bits_v=3, block_size=2048, grad_dtype=solo.SOLO_GRAD_BF16)
+    assert solo.solo_multi_units(arr, len(sizes), big) == 0
+    assert solo.solo_multi_table_build(arr, len(sizes), big, buf.ctypes.data, nbytes, check=False)[0] == solo.SOLO_E_UNSUPPORTED
+    assert solo.solo_num_blocks(5000, 2048) == 3
+    assert solo.solo_state_bytes(4096, big) == 4 * (256 + 410) + 12 * 2
+
+
 def test_product_does_not_import_the_oracle():
     """The library and its binding must not reach into oracle/ (tests, smoke and the
     benchmark's cpu_baseline leg are the only users)."""
