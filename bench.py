@@ -338,6 +338,13 @@ def main():
     def frac_of(ms):
         return (bpp * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if ms else None
 
+    # the kernel that takes the time (the library picks it from the format, the size and the launch)
+    if w.block_size == 2048:
+        kernel_name = "solo::big_wide_kernel"
+    elif args.launch == "multi":
+        kernel_name = "solo::multi_chunk_kernel" if (w.grad_dtype == "fp32" and w.m_codebook == "linear") else "solo::multi_kernel"
+    else:
+        kernel_name = "solo::step_kernel"
     out = {
         "metric": "updated_params_per_sec", "value": n / (wall / args.steps), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -350,7 +357,7 @@ def main():
                    "bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name) if (args.variant, args.launch) == ("adamw", "flat") else None,
-                     "kernel": "solo::step_kernel", "kernel_ms": avg_kernel_s * 1e3,
+                     "kernel": kernel_name, "kernel_ms": avg_kernel_s * 1e3,
                      "stream_probe": probe},
         # the warm-up time of every allocation that was tried, which one the timed steps ran on, and
         # the roofline fraction the warm-up steps gave on the first and on the fastest of them

@@ -1,13 +1,17 @@
 // The fused SOLO AdamW step for blocks of 2048 elements (the large-block setting of the paper's
 // block-size comparison, Sec. 4.2), gfx950, wave64.
 //
-// A block of 2048 elements is held by one workgroup of four wavefronts, 512 elements each, eight
-// consecutive elements per lane: the element-wise part (decode by table look-up, both EMAs, the
-// parameter, the encoders, the 32-bit words of the code streams) is that of the 512-element
-// iterations of solo_step.h, one iteration per wavefront, and runs without any exchange between
-// the wavefronts.  What a block of this size changes is the block statistics:
-//   * Delta_m' and Delta_v' are maxima over four wavefronts: DPP inside a row, four lane reads
-//     across the rows, four words of LDS and one barrier across the wavefronts;
+// A block of 2048 elements is held by one workgroup.  Two forms:
+//   * a full block: two wavefronts, 1024 elements each, sixteen consecutive elements per lane
+//     (step_block_wide, big_wide_kernel);
+//   * the shorter last block of a buffer: four wavefronts, 512 elements each, eight per lane,
+//     bounds checks on every element (step_block_big, big_kernel; a launch of its own).
+// The element-wise part (decode by table look-up, both EMAs, the parameter, the encoders, the
+// 32-bit words of the code streams) is that of an iteration of solo_step.h, one iteration per
+// wavefront, and runs without any exchange between the wavefronts.  What a block of this size
+// changes is the block statistics:
+//   * Delta_m' and Delta_v' are maxima over the wavefronts: DPP inside a row, four lane reads
+//     across the rows, a few words of LDS and one barrier across the wavefronts;
 //   * the p-quantile is the rank-205 element of 2048 values (p = 0.1), far too deep for rounds
 //     of "extract the minimum".  It is found by a radix select on the bit patterns (non-negative
 //     floats order like their bits): three passes over 11 + 10 + 10 bits, each a histogram of the
@@ -15,11 +19,13 @@
 //     (DPP scans) that every wavefront runs for itself to find the bin that holds the rank.
 //     After the third pass the prefix is the order statistic itself, multiplicities included,
 //     exactly.  Four barriers per block in all.
-//   * the base alpha, the division and the level tables are computed by every wavefront (every
+//   * the base alpha, the divisions and the level tables are computed by every wavefront (every
 //     16 lanes) for itself: cheaper than another barrier.
-// One workgroup per block, every wavefront stages and writes back the words of its own 512
-// elements (whole 128-byte lines for 2- and 4-bit codes; ten-to-a-word codes by one atomic XOR
-// per word at the memory side, since a block does not end on a word).
+// LDS sets the number of workgroups on a CU, and that the speed (measured on MI355X: 17.3 ms for
+// 6.7e9 parameters at 3.5 wavefronts per SIMD, 15.7 ms at 5), so the histograms are kept small:
+// see BigLayout.  Every wavefront stages and writes back the words of its own elements (whole
+// 128-byte lines for 2- and 4-bit codes; ten-to-a-word codes by one atomic XOR per word at the
+// memory side, since a wavefront's share does not end on a word).
 #pragma once
 #include "solo_step.h"
 
@@ -29,14 +35,18 @@ constexpr int kBigBlock = 2048;
 constexpr int kBigWaves = kBigBlock / kIter;      // 4 wavefronts, one workgroup per block
 static_assert(kBigWaves == 4, "one workgroup of four wavefronts per block");
 
-// LDS of a workgroup (32-bit words).  `work` first serves the four wavefronts as the staging
-// areas of their layout transpositions (64 x 12 words each), then, behind the barrier of the block
-// maxima, the whole workgroup as the histograms of the selection.  A histogram keeps 4 pad words
-// after the 32 (16) bins that one lane sums, so that the lanes' 128-bit reads spread over the banks.
+// LDS of a workgroup (32-bit words).  `work` first serves the wavefronts as the staging areas of
+// their layout transpositions, then, behind the barrier of the block maxima, the whole workgroup as
+// the histograms of the selection: 2048 bins of 32 bits for the first pass, and 1024 words whose
+// lower halves count the second pass and whose upper halves count the third (a count never exceeds
+// 2048, so the halves do not carry into each other, and a wavefront that is still reading the
+// second pass's halves is not disturbed by one that already counts the third).  Four pad words
+// follow every 64 bins: the rows that the 64 lanes sum with 128-bit reads (32 or 16 bins each)
+// then start in 16 different groups of four banks.
 struct BigLayout {
     static constexpr int kStage = 64 * kColStride;            // per wavefront
-    static constexpr int kHist0 = 0, kHist1 = 2048 + 4 * 64, kHist2 = kHist1 + 1024 + 4 * 64;
-    static constexpr int kWork = kHist2 + 1024 + 4 * 64;      // 4864 words
+    static constexpr int kHist0 = 0, kHist12 = 2048 + 2048 / 64 * 4;
+    static constexpr int kWork = kHist12 + 1024 + 1024 / 64 * 4;   // 3264 words
     static constexpr int kOffImgM = 0;                        // per wavefront: its words of each code stream (<= 64, + 1)
     static constexpr int kOffImgV = 68;
     static constexpr int kOffTv = 144;                        // level tables, 64-byte aligned
@@ -67,45 +77,51 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x)
     return x;
 }
 
-// The rank-th smallest (1-based, uniform over the workgroup) of the 8 keys that each of the 256
-// threads holds: bit patterns of non-negative floats, +inf for absent elements (the rank never
-// reaches those).  Radix select over 11 + 10 + 10 bits.  A pass: every thread adds its keys that
-// still match the selected prefix to the pass's histogram (in `work`, zeroed before
+// The rank-th smallest (1-based, uniform over the workgroup) of the NK keys that each thread of
+// the workgroup holds (2048 in all): bit patterns of non-negative floats, +inf for absent elements
+// (the rank never reaches those).  Radix select over 11 + 10 + 10 bits.  A pass: every thread adds
+// its keys that still match the selected prefix to the pass's histogram (in `work`, zeroed before
 // the workgroup's previous barrier), one barrier, and then every wavefront finds the bin of the
 // rank for itself: a lane sums 32 (16) consecutive bins, a prefix sum over the wavefront names
 // the lane whose bins hold the rank, and a second prefix sum over that lane's bins, one per
 // lane, names the bin.  No exchange between the wavefronts beyond the histogram.
-__device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[8], uint32_t rank, uint32_t lane, uint32_t *work)
+template <int NK>
+__device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[NK], uint32_t rank, uint32_t lane, uint32_t *work)
 {
     uint32_t prefix = 0;                          // the bits selected so far (bit 31 of a key is 0)
 #pragma unroll
     for (int pass = 0; pass < 3; ++pass) {
         constexpr int kBits[3] = {11, 10, 10}, kShift[3] = {20, 10, 0};
-        constexpr int kOff[3] = {BigLayout::kHist0, BigLayout::kHist1, BigLayout::kHist2};
         const int bits = kBits[pass], sh = kShift[pass];
         const uint32_t bins = 1u << bits, per = bins / 64u;          // 32, 16, 16 bins per lane
-        const int lper = bits - 6;                                   // log2(per)
-        uint32_t *const h = work + kOff[pass];
+        uint32_t *const h = work + (pass == 0 ? BigLayout::kHist0 : BigLayout::kHist12);
+        const uint32_t one = pass == 2 ? 0x10000u : 1u;               // the third pass counts in the upper halves
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NK; ++j) {
             const bool match = pass == 0 || (key[j] >> (sh + bits)) == prefix;
             const uint32_t b = (key[j] >> sh) & (bins - 1u);
-            if (match) atomicAdd(&h[b + ((b >> lper) << 2)], 1u);
+            if (match) atomicAdd(&h[b + ((b >> 6) << 2)], one);
         }
         __syncthreads();
+        // this lane's row of bins: `per` words from word per * lane, plus the pads in front of it
+        const uint32_t row = per * lane + ((lane * per) >> 6 << 2);
         uint32_t s = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             if ((uint32_t)(4 * i) < per) {
-                const uint4 c4 = reinterpret_cast<const uint4 *>(h)[lane * (per / 4u + 1u) + (uint32_t)i];
+                const uint4 c4 = *reinterpret_cast<const uint4 *>(h + row + 4 * i);
                 s += (c4.x + c4.y) + (c4.z + c4.w);
             }
         }
+        if (pass == 1) s &= 0xFFFFu;
+        if (pass == 2) s >>= 16;
         const uint32_t incl = wave_inclusive_sum(s);
         const uint64_t holder = __builtin_amdgcn_ballot_w64(incl - s < rank && rank <= incl);   // one lane
         const uint32_t sel = (uint32_t)__builtin_ctzll(holder | (1ull << 63));
         rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl - s), (int)sel);
-        const uint32_t c = lane < per ? h[sel * (per + 4u) + lane] : 0u;
+        uint32_t c = lane < per ? h[per * sel + ((sel * per) >> 6 << 2) + lane] : 0u;
+        if (pass == 1) c &= 0xFFFFu;
+        if (pass == 2) c >>= 16;
         const uint32_t incl2 = wave_inclusive_sum(c);
         const uint64_t holder2 = __builtin_amdgcn_ballot_w64(incl2 - c < rank && rank <= incl2);
         const uint32_t sel2 = (uint32_t)__builtin_ctzll(holder2 | (1ull << 63));
@@ -301,7 +317,7 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     uint32_t key[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) key[j] = (TAIL && !ok[j]) ? kInfBits : f2u(vh[j]);
-    const uint32_t xp_bits = select_rank(key, rank, lane, work);
+    const uint32_t xp_bits = select_rank<8>(key, rank, lane, work);
 
     // ---- encoder constants (every 16 lanes for themselves), codes, the wavefront's words
     const uint32_t lig = lane & 15u, gshift = lane & 16u;
@@ -334,7 +350,312 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     if (tid == 0) { a.m_scale[blk] = dm; a.v_scale[blk] = dv; a.v_base[blk] = codec.alpha; }
 }
 
-// One workgroup per block of 2048 elements.
+// ---- the wide form of a full block: two wavefronts, 16 consecutive elements per lane
+//
+// The element-wise part is that of one 1024-element iteration of the wide streaming path
+// (step_tile16), the block statistics are those of step_block_big() with two wavefronts instead of
+// four.  What is done once per lane and block (level tables, the two divisions, the base, the
+// hash of a group of eight, the scans of the selection) is spread over twice as many elements, and
+// the scans are run by two wavefronts instead of four.
+constexpr int kWideBigWaves = kBigBlock / kIter16;
+static_assert(kWideBigWaves == 2, "one workgroup of two wavefronts per block");
+
+#ifndef SOLO_BIG_WIDE
+#define SOLO_BIG_WIDE 1            // (tuning builds: 0 runs full blocks on four wavefronts, too)
+#endif
+
+struct WideBigLayout {
+    static constexpr int kStage = 64 * kColStride16;          // per wavefront: staging of the layout transpositions
+    static constexpr int kOffImgM = 0;                        // per wavefront: its words of each code stream (<= 128, + 4)
+    static constexpr int kOffImgV = 132;
+    static constexpr int kOffTv = 272;                        // level tables, 64-byte aligned
+    static constexpr int kOffTm = 288;
+    static constexpr int kSlab = 304;
+};
+static_assert(BigLayout::kWork >= kWideBigWaves * WideBigLayout::kStage, "the staging areas lie inside the work area");
+static_assert(288 * 4 <= WideBigLayout::kStage, "the padded transposition fits a staging area");
+
+template <int BM, int BV, bool BF16, bool MDE, bool EXT>
+__device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_t blk, const uint32_t lane,
+                                                const uint32_t wave, uint32_t *const slab, uint32_t *const work,
+                                                uint32_t *const xch, const uint32_t *const lds_de)
+{
+    constexpr int L = (1 << (BM - 1)) - 1;
+    constexpr int K = (1 << BV) - 1;
+    constexpr int CM = 32 / BM, CV = 32 / BV;
+    constexpr int VT = K + 1;
+    constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
+    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
+    constexpr bool kDeTable = MDE && BM >= 3;
+    constexpr int KM = CM == 16 ? 1 : 2, KV = CV == 16 ? 1 : 2;      // words of a stream per lane (64 x K >= words of 1024 elements)
+
+    const uint32_t tid = wave * 64u + lane;
+    const uint64_t ew0 = blk * kBigBlock + (uint64_t)wave * kIter16;  // first element of this wavefront
+    const uint64_t e0 = ew0 + lane * 16u;                             // first element of this lane
+    uint32_t *const img_m = slab + WideBigLayout::kOffImgM, *const img_v = slab + WideBigLayout::kOffImgV;
+    float *const my_tv = reinterpret_cast<float *>(slab + WideBigLayout::kOffTv);
+    float *const my_tm = reinterpret_cast<float *>(slab + WideBigLayout::kOffTm);
+    const uint32_t tv_addr = lds_addr(my_tv), tm_addr = lds_addr(my_tm);
+
+    // ---- loads: parameters and gradients, the wavefront's code words, the block's scalars
+    RawPG16<BF16> raw = load_pg16<BF16>(a, ew0, lane);
+    const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;
+    float4 *const stage = reinterpret_cast<float4 *>(work + wave * WideBigLayout::kStage);
+    float4 *const st4_c = stage + (lane + lane / 8u);       // + 72 k
+    float4 *const st4_l = stage + (4u * lane + lane / 2u);  // + c
+    float4 *const st2_c = stage + (lane + lane / 8u);       // + 72 k
+    float4 *const st2_l = stage + (2u * lane + lane / 4u);  // + c
+    // words of the wavefront's 1024 elements: the first may start inside a word (ten-to-a-word
+    // codes); all of them exist, the block is a full one
+    const uint64_t gm_lo = ew0 / CM, gv_lo = ew0 / CV;
+    const uint32_t rm0 = (uint32_t)(ew0 - gm_lo * CM), rv0 = (uint32_t)(ew0 - gv_lo * CV);   // slot of the first element
+    const uint32_t nwm = (rm0 + kIter16 + CM - 1) / CM, nwv = (rv0 + kIter16 + CV - 1) / CV;  // words touched (<= 128)
+    uint32_t own_m[KM], own_v[KV];
+#pragma unroll
+    for (int k = 0; k < KM; ++k) {
+        own_m[k] = 0;
+        if (lane + 64u * k < nwm) own_m[k] = a.m_words[gm_lo + lane + 64u * k];
+    }
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+        own_v[k] = 0;
+        if (lane + 64u * k < nwv) own_v[k] = a.v_words[gv_lo + lane + 64u * k];
+    }
+    const float dm_old = a.m_scale[blk], dv_old = a.v_scale[blk], al_old = a.v_base[blk];
+#pragma unroll
+    for (int k = 0; k < KM; ++k) {
+        if (BM == 3) own_m[k] &= 0x3FFFFFFFu;
+        img_m[lane + 64u * k] = own_m[k];
+    }
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+        if (BV == 3) own_v[k] &= 0x3FFFFFFFu;
+        img_v[lane + 64u * k] = own_v[k];
+    }
+    if (lane < 4) { img_m[64 * KM + lane] = 0; img_v[64 * KV + lane] = 0; }
+
+    // ---- level tables of the block (every wavefront its own copy)
+    {
+        const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
+        const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
+        if (lane < (uint32_t)VT) my_tv[lane] = log_level<BV>(lane, P1, P2, P4, P8) * dv_old;
+        if (lane < (uint32_t)MT) my_tm[lane] = MDE ? DeLevels<BM>::level(lane) * dm_old : (float)((int)lane - L) * s_m;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // word and slot of the first code of the lane's two runs of 8 inside the wavefront's words
+    uint32_t wm[2], sm[2], wv[2], sv[2];
+    uint32_t mc8[2], vc8[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const uint32_t qm = rm0 + lane * 16u + 8u * r, qv = rv0 + lane * 16u + 8u * r;   // < 1040: e / 10 by multiplication
+        wm[r] = (CM == 10) ? __umul24(qm, 52429u) >> 19 : qm / CM; sm[r] = qm - wm[r] * CM;
+        wv[r] = (CV == 10) ? __umul24(qv, 52429u) >> 19 : qv / CV; sv[r] = qv - wv[r] * CV;
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        // (2-bit codes: both runs of the lane lie in one word)
+        const uint32_t mw0 = img_m[wm[BM == 2 ? 0 : r]], mw1 = (BM == 3) ? img_m[wm[r] + 1] : 0u;
+        const uint32_t vw0 = img_v[wv[BV == 2 ? 0 : r]], vw1 = (BV == 3) ? img_v[wv[r] + 1] : 0u;
+        mc8[r] = extract8<BM>(mw0, mw1, BM == 2 ? 8u * r : sm[r]) & (uint32_t)((1ull << (8 * BM)) - 1ull);
+        vc8[r] = extract8<BV>(vw0, vw1, BV == 2 ? 8u * r : sv[r]) & (uint32_t)((1ull << (8 * BV)) - 1ull);
+    }
+
+    // ---- coalesced layout -> 16 consecutive elements per lane
+    float p[16], g[16];
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) st4_c[72 * k] = raw.p[k];
+        wave_lds_sync();
+        float4 t[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) t[c] = st4_l[c];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { p[4 * c] = t[c].x; p[4 * c + 1] = t[c].y; p[4 * c + 2] = t[c].z; p[4 * c + 3] = t[c].w; }
+        wave_lds_sync();
+        if (BF16) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+                st2_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+            wave_lds_sync();
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const float4 x = st2_l[c];
+                const uint32_t w[4] = {f2u(x.x), f2u(x.y), f2u(x.z), f2u(x.w)};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    g[8 * c + 2 * i] = u2f(w[i] << 16);
+                    g[8 * c + 2 * i + 1] = u2f(w[i] & 0xFFFF0000u);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < (BF16 ? 2 : 4); ++k)
+                st4_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+            wave_lds_sync();
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float4 x = st4_l[c];
+                g[4 * c] = x.x; g[4 * c + 1] = x.y; g[4 * c + 2] = x.z; g[4 * c + 3] = x.w;
+            }
+        }
+    }
+    if (EXT) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
+    }
+
+    // ---- dequantize (table look-up), EMA, parameter
+    float mh[16], vh[16];
+    float m_absmax = 0.0f, v_max = 0.0f;
+    const float kb = a.belief ? 1.0f : 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int r = j / 8, jj = j % 8;
+        const uint32_t om = (jj == 0) ? (mc8[r] << 2) : (mc8[r] >> (BM * jj - 2));
+        const uint32_t ov = (jj == 0) ? (vc8[r] << 2) : (vc8[r] >> (BV * jj - 2));
+        const float mt = lds_f32(tm_addr | (om & MIDX));
+        const float vt = lds_f32(tv_addr | (ov & VIDX));
+        mh[j] = __builtin_fmaf(a.beta1, mt, a.omb1 * g[j]);
+        if (EXT) {
+            const float d = __builtin_fmaf(-kb, mh[j], g[j]);
+            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (d * d)) + a.eps_state;
+        } else {
+            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (g[j] * g[j]));
+        }
+        const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
+        p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
+        m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
+        v_max = __builtin_fmaxf(v_max, vh[j]);
+    }
+    // ---- new parameters back to the coalesced layout, streamed out
+    wave_lds_sync();
+    if (EXT && a.param_bf16) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t h0 = pack_bf16(p[8 * c], p[8 * c + 1]), h1 = pack_bf16(p[8 * c + 2], p[8 * c + 3]);
+            const uint32_t h2 = pack_bf16(p[8 * c + 4], p[8 * c + 5]), h3 = pack_bf16(p[8 * c + 6], p[8 * c + 7]);
+            st2_l[c] = make_float4(u2f(h0), u2f(h1), u2f(h2), u2f(h3));
+        }
+        wave_lds_sync();
+        uint16_t *hp = a.param_bf16 + ew0 + lane * 8u;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) stream_store_f4(reinterpret_cast<float *>(hp + 512 * k), st2_c[72 * k]);
+        wave_lds_sync();
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) st4_l[c] = make_float4(p[4 * c], p[4 * c + 1], p[4 * c + 2], p[4 * c + 3]);
+    wave_lds_sync();
+    {
+        float *pp = a.param + ew0 + lane * 4u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st4_c[72 * k]);
+    }
+
+    // ---- the work area becomes the histograms of the selection: a wavefront clears its own staging
+    // area (it is done with it; the other may still be using its own) and its share of the rest
+    {
+        uint4 *const own = reinterpret_cast<uint4 *>(work + wave * WideBigLayout::kStage);
+        wave_lds_sync();
+        constexpr int kOwn = WideBigLayout::kStage / 4;                                     // 128-bit words
+#pragma unroll
+        for (int i = 0; i < (kOwn + 63) / 64; ++i)
+            if (lane + 64u * (uint32_t)i < (uint32_t)kOwn) own[lane + 64u * (uint32_t)i] = make_uint4(0, 0, 0, 0);
+        constexpr int kRest = (BigLayout::kWork - kWideBigWaves * WideBigLayout::kStage) / 4;
+        uint4 *const rest = reinterpret_cast<uint4 *>(work + kWideBigWaves * WideBigLayout::kStage);
+        for (uint32_t i = tid; i < (uint32_t)kRest; i += kWideBigWaves * 64) rest[i] = make_uint4(0, 0, 0, 0);
+    }
+
+    // ---- block maxima over the two wavefronts
+    {
+        const uint32_t wm_max = wave_max(f2u(m_absmax)), wv_max = wave_max(f2u(v_max));
+        if (lane == 0) { xch[wave] = wm_max; xch[2 + wave] = wv_max; }
+    }
+    __syncthreads();
+    float dm = u2f(umax(xch[0], xch[1]));
+    float dv = u2f(umax(xch[2], xch[3]));
+    if (dm < kTiny) dm = 0.0f;
+    if (dv < kTiny) dv = 0.0f;
+
+    // ---- the r-th smallest v^ of the block
+    uint32_t key[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) key[j] = f2u(vh[j]);
+    const uint32_t xp_bits = select_rank<16>(key, a.rank_full, lane, work);
+
+    // ---- encoder constants (every 16 lanes for themselves), codes, the wavefront's words
+    const uint32_t lig = lane & 15u, gshift = lane & 16u;
+    uint32_t de_base = 0;
+    if (kDeTable) de_base = lds_addr(lds_de) - 16u * DeBuckets<BM>::kLo;
+    const BlockCodec codec = block_codec<BV, 16, L, MDE>(xp_bits, dm, dv, lane, lig, gshift);
+    uint32_t m_word = 0, v_word = 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        uint32_t m8, v8;
+        encode_run<BM, BV, MDE, false>(a, e0 + 8u * r, mh + 8 * r, vh + 8 * r, nullptr, codec, de_base, m8, v8);
+        // 3-bit codes share words between lanes: XOR turns this lane's old fields into the new
+        // ones and leaves the neighbours' alone.  2- and 4-bit words belong to one lane.
+        if (BM == 3) {
+            const uint32_t xm = mc8[r] ^ m8;
+            atomicXor(&img_m[wm[r]], (xm << (3u * sm[r])) & 0x3FFFFFFFu);
+            atomicXor(&img_m[wm[r] + 1], (uint32_t)(((uint64_t)xm << (3u * sm[r])) >> 30));
+        } else if (BM == 4) {
+            img_m[wm[r]] = m8;
+        } else {
+            m_word |= m8 << (16 * r);
+            if (r == 1) img_m[wm[0]] = m_word;
+        }
+        if (BV == 3) {
+            const uint32_t xv = vc8[r] ^ v8;
+            atomicXor(&img_v[wv[r]], (xv << (3u * sv[r])) & 0x3FFFFFFFu);
+            atomicXor(&img_v[wv[r] + 1], (uint32_t)(((uint64_t)xv << (3u * sv[r])) >> 30));
+        } else if (BV == 4) {
+            img_v[wv[r]] = v8;
+        } else {
+            v_word |= v8 << (16 * r);
+            if (r == 1) img_v[wv[0]] = v_word;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < KM; ++k) {
+        if (lane + 64u * k < nwm) {
+            const uint32_t fin = img_m[lane + 64u * k];
+            if (BM != 3) a.m_words[gm_lo + lane + 64u * k] = fin;
+            else if (fin != own_m[k]) atomicXor(&a.m_words[gm_lo + lane + 64u * k], fin ^ own_m[k]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+        if (lane + 64u * k < nwv) {
+            const uint32_t fin = img_v[lane + 64u * k];
+            if (BV != 3) a.v_words[gv_lo + lane + 64u * k] = fin;
+            else if (fin != own_v[k]) atomicXor(&a.v_words[gv_lo + lane + 64u * k], fin ^ own_v[k]);
+        }
+    }
+    if (tid == 0) { a.m_scale[blk] = dm; a.v_scale[blk] = dv; a.v_base[blk] = codec.alpha; }
+}
+
+// One workgroup of two wavefronts per full block of 2048 elements.
+template <int BM, int BV, bool BF16, bool MDE, bool EXT>
+__global__ __launch_bounds__(kWideBigWaves * 64, kWideWaves)
+void big_wide_kernel(const StepArgs a)
+{
+    constexpr int kDeWords = (MDE && BM >= 3) ? 4 * DeBuckets<BM>::N : 16;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_work[BigLayout::kWork];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWideBigWaves * WideBigLayout::kSlab];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[4];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
+    load_de_table<BM, MDE, kDeWords>(lds_de);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    step_block_wide<BM, BV, BF16, MDE, EXT>(a, blockIdx.x, lane, wave, lds_slab + wave * WideBigLayout::kSlab,
+                                            lds_work, lds_xch, lds_de);
+}
+
+// One workgroup of four wavefronts per block of 2048 elements, from block a.tail_tile0 on.
 template <int BM, int BV, bool BF16, bool MDE, bool EXT>
 __global__ __launch_bounds__(kBigWaves * 64, SOLO_MIN_WAVES)
 void big_kernel(const StepArgs a)
@@ -347,25 +668,40 @@ void big_kernel(const StepArgs a)
     load_de_table<BM, MDE, kDeWords>(lds_de);
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint64_t blk = blockIdx.x;
+    const uint64_t blk = a.tail_tile0 + blockIdx.x;
     uint32_t *const slab = lds_slab + wave * BigLayout::kSlab;
-    if ((blk + 1) * kBigBlock <= a.n)
-        step_block_big<BM, BV, BF16, MDE, false, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
-    else
-        step_block_big<BM, BV, BF16, MDE, true, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
+    if constexpr (!SOLO_BIG_WIDE) {
+        if ((blk + 1) * kBigBlock <= a.n) {
+            step_block_big<BM, BV, BF16, MDE, false, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
+            return;
+        }
+    }
+    step_block_big<BM, BV, BF16, MDE, true, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
 }
 
 template <int BM, bool MDE>
 hipError_t launch_big(uint32_t bits_v, bool bf16, const StepArgs &args, hipStream_t stream);
 
+// Full blocks run on two wavefronts each; a shorter last block is a launch of its own, one
+// workgroup of four wavefronts with bounds checks on every element.
 template <int BM, bool MDE>
 hipError_t launch_big_impl(uint32_t bits_v, bool bf16, const StepArgs &args, hipStream_t stream)
 {
-    const uint64_t grid = (args.n + kBigBlock - 1) / kBigBlock;
-    if (grid == 0 || grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const uint64_t full = args.n / kBigBlock, blocks = (args.n + kBigBlock - 1) / kBigBlock;
+    if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool ext = args.param_bf16 || args.grad_scale || args.belief || args.l2 != 0.0f;
+    const uint64_t wide_blocks = SOLO_BIG_WIDE ? full : 0;
+    StepArgs rest = args;
+    rest.tail_tile0 = wide_blocks;               // the four-wavefront kernel starts behind them
 #define SOLO_LAUNCH(BV_, BF_, EXT_)                                                                 \
-    hipLaunchKernelGGL((big_kernel<BM, BV_, BF_, MDE, EXT_>), dim3((uint32_t)grid), dim3(kBigWaves * 64), 0, stream, args)
+    do {                                                                                            \
+        if (wide_blocks)                                                                            \
+            hipLaunchKernelGGL((big_wide_kernel<BM, BV_, BF_, MDE, EXT_>), dim3((uint32_t)wide_blocks),    \
+                               dim3(kWideBigWaves * 64), 0, stream, args);                          \
+        if (blocks > wide_blocks)                                                                   \
+            hipLaunchKernelGGL((big_kernel<BM, BV_, BF_, MDE, EXT_>), dim3((uint32_t)(blocks - wide_blocks)), \
+                               dim3(kBigWaves * 64), 0, stream, rest);                              \
+    } while (0)
 #define SOLO_CASE(BV_)                                                                              \
     if (bits_v == BV_) {                                                                            \
         if (bf16) { if (ext) SOLO_LAUNCH(BV_, true, true); else SOLO_LAUNCH(BV_, true, false); }    \
