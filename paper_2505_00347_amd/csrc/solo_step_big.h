@@ -14,11 +14,11 @@
 //     across the rows, a few words of LDS and one barrier across the wavefronts;
 //   * the p-quantile is the rank-205 element of 2048 values (p = 0.1), far too deep for rounds
 //     of "extract the minimum".  It is found by a radix select on the bit patterns (non-negative
-//     floats order like their bits): three passes over 11 + 10 + 10 bits, each a histogram of the
-//     keys that still match the selected prefix (LDS atomics), one barrier, and two prefix sums
-//     (DPP scans) that every wavefront runs for itself to find the bin that holds the rank.
-//     After the third pass the prefix is the order statistic itself, multiplicities included,
-//     exactly.  Four barriers per block in all.
+//     floats order like their bits): four passes over 8 + 8 + 8 + 7 bits, each a histogram of the
+//     keys that still match the selected prefix (LDS atomics), one barrier, a prefix sum (DPP
+//     scan) by which one wavefront finds the bin that holds the rank, and a second barrier.
+//     After the last pass the prefix is the order statistic itself, multiplicities included,
+//     exactly.  Nine barriers per block in all.
 //   * the base alpha, the divisions and the level tables are computed by every wavefront (every
 //     16 lanes) for itself: cheaper than another barrier.
 // LDS sets the number of workgroups on a CU, and that the speed (measured on MI355X: 17.3 ms for
@@ -37,16 +37,25 @@ static_assert(kBigWaves == 4, "one workgroup of four wavefronts per block");
 
 // LDS of a workgroup (32-bit words).  `work` first serves the wavefronts as the staging areas of
 // their layout transpositions, then, behind the barrier of the block maxima, the whole workgroup as
-// the histograms of the selection: 2048 bins of 32 bits for the first pass, and 1024 words whose
-// lower halves count the second pass and whose upper halves count the third (a count never exceeds
-// 2048, so the halves do not carry into each other, and a wavefront that is still reading the
-// second pass's halves is not disturbed by one that already counts the third).  Four pad words
-// follow every 64 bins: the rows that the 64 lanes sum with 128-bit reads (32 or 16 bins each)
-// then start in 16 different groups of four banks.
+// the histograms of the selection (four passes over 8 + 8 + 8 + 7 bits).
+// The second moments of a block that has been trained for a while sit in a few tight clusters, one
+// per level of the previous code, so most of the 64 lanes of an instruction add to the same one or
+// two bins, and LDS applies the adds to one bank one after the other (measured on MI355X with one
+// counter per bin: the step slowed down by half between the first and the thousandth update of a
+// state, all of it LDS bank conflicts).  Every bin therefore has 8 (4) counters in neighbouring
+// words, i.e. in different banks, and a lane always uses the one its number selects.
+//   hist A: 256 bins x 8 counters; the lower halves of its words count the first pass, the upper
+//           halves the second (a count is at most 2048, so the halves do not carry into each
+//           other, and a wavefront that is still reading the lower halves is not disturbed by one
+//           that already counts the next pass in the upper ones);
+//   hist B: 256 bins x 4 counters; lower halves: third pass, upper halves: fourth (128 bins).
+// Four pad words follow every 64 words: the rows that the 64 lanes sum with 128-bit reads (32 or
+// 16 words each) then start in 16 different groups of four banks.
 struct BigLayout {
     static constexpr int kStage = 64 * kColStride;            // per wavefront
-    static constexpr int kHist0 = 0, kHist12 = 2048 + 2048 / 64 * 4;
-    static constexpr int kWork = kHist12 + 1024 + 1024 / 64 * 4;   // 3264 words
+    static constexpr int kHistA = 0, kHistB = 2048 + 2048 / 64 * 4;
+    static constexpr int kHists = kHistB + 1024 + 1024 / 64 * 4;                // 3264 words
+    static constexpr int kWork = kHists > 4 * kStage ? kHists : 4 * kStage;
     static constexpr int kOffImgM = 0;                        // per wavefront: its words of each code stream (<= 64, + 1)
     static constexpr int kOffImgV = 68;
     static constexpr int kOffTv = 144;                        // level tables, 64-byte aligned
@@ -79,54 +88,67 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x)
 
 // The rank-th smallest (1-based, uniform over the workgroup) of the NK keys that each thread of
 // the workgroup holds (2048 in all): bit patterns of non-negative floats, +inf for absent elements
-// (the rank never reaches those).  Radix select over 11 + 10 + 10 bits.  A pass: every thread adds
-// its keys that still match the selected prefix to the pass's histogram (in `work`, zeroed before
-// the workgroup's previous barrier), one barrier, and then every wavefront finds the bin of the
-// rank for itself: a lane sums 32 (16) consecutive bins, a prefix sum over the wavefront names
-// the lane whose bins hold the rank, and a second prefix sum over that lane's bins, one per
-// lane, names the bin.  No exchange between the wavefronts beyond the histogram.
+// (the rank never reaches those).  Radix select over 8 + 8 + 8 + 7 bits.  A pass: every thread
+// adds its keys that still match the selected prefix to its counters of the pass's histogram (in
+// `work`, zeroed before the workgroup's first barrier), one barrier, and then one wavefront finds
+// the bin of the rank: a lane sums the counters of its four (two) consecutive bins, a prefix sum
+// over the wavefront names the lane whose bins hold the rank, and that lane's bin sums name the
+// bin; `res` (8 words of LDS) hands bin and rank to the other wavefronts behind a second barrier.
 template <int NK>
-__device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[NK], uint32_t rank, uint32_t lane, uint32_t *work)
+__device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[NK], uint32_t rank, uint32_t lane, uint32_t wave,
+                                                uint32_t *work, uint32_t *res)
 {
-    uint32_t prefix = 0;                          // the bits selected so far (bit 31 of a key is 0)
+    uint32_t prefix = 0;
 #pragma unroll
-    for (int pass = 0; pass < 3; ++pass) {
-        constexpr int kBits[3] = {11, 10, 10}, kShift[3] = {20, 10, 0};
+    for (int pass = 0; pass < 4; ++pass) {
+        constexpr int kBits[4] = {8, 8, 8, 7}, kShift[4] = {23, 15, 7, 0};      // (bit 31 of a key is 0)
         const int bits = kBits[pass], sh = kShift[pass];
-        const uint32_t bins = 1u << bits, per = bins / 64u;          // 32, 16, 16 bins per lane
-        uint32_t *const h = work + (pass == 0 ? BigLayout::kHist0 : BigLayout::kHist12);
-        const uint32_t one = pass == 2 ? 0x10000u : 1u;               // the third pass counts in the upper halves
+        const int lr = pass < 2 ? 3 : 2;                                        // log2(counters per bin)
+        const uint32_t R = 1u << lr;
+        uint32_t *const h = work + (pass < 2 ? BigLayout::kHistA : BigLayout::kHistB);
+        const uint32_t one = (pass & 1) ? 0x10000u : 1u;
+        const uint32_t mine = lane & (R - 1u);
 #pragma unroll
         for (int j = 0; j < NK; ++j) {
             const bool match = pass == 0 || (key[j] >> (sh + bits)) == prefix;
-            const uint32_t b = (key[j] >> sh) & (bins - 1u);
-            if (match) atomicAdd(&h[b + ((b >> 6) << 2)], one);
+            const uint32_t w = ((((key[j] >> sh) & ((1u << bits) - 1u))) << lr) | mine;
+            if (match) atomicAdd(&h[w + ((w >> 6) << 2)], one);
         }
         __syncthreads();
-        // this lane's row of bins: `per` words from word per * lane, plus the pads in front of it
-        const uint32_t row = per * lane + ((lane * per) >> 6 << 2);
-        uint32_t s = 0;
+        // One wavefront finds the bin (wavefronts 0 and 1 take turns) and leaves it and the rank
+        // inside it in LDS for the others: a second barrier costs less than every wavefront
+        // summing the whole histogram for itself.
+        if (wave == (uint32_t)(pass & 1)) {
+        // this lane's bins: 4 of 256 (2 of 128), `per` words from word per * lane, behind the pads in front of it
+        const uint32_t nb = (1u << bits) / 64u;                                 // bins per lane
+        const uint32_t per = nb * R;                                            // words per lane: 32, 32, 16, 8
+        const uint32_t row = per * lane + (((per * lane) >> 6) << 2);
+        uint32_t c[4] = {0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if ((uint32_t)(4 * i) < per) {
-                const uint4 c4 = *reinterpret_cast<const uint4 *>(h + row + 4 * i);
-                s += (c4.x + c4.y) + (c4.z + c4.w);
+        for (uint32_t k = 0; k < nb; ++k) {
+#pragma unroll
+            for (uint32_t i = 0; i < R / 4u; ++i) {
+                const uint4 c4 = *reinterpret_cast<const uint4 *>(h + row + k * R + 4u * i);
+                c[k] += (c4.x + c4.y) + (c4.z + c4.w);
             }
+            c[k] = (pass & 1) ? c[k] >> 16 : c[k] & 0xFFFFu;
         }
-        if (pass == 1) s &= 0xFFFFu;
-        if (pass == 2) s >>= 16;
+        const uint32_t s = (c[0] + c[1]) + (c[2] + c[3]);
         const uint32_t incl = wave_inclusive_sum(s);
         const uint64_t holder = __builtin_amdgcn_ballot_w64(incl - s < rank && rank <= incl);   // one lane
         const uint32_t sel = (uint32_t)__builtin_ctzll(holder | (1ull << 63));
         rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl - s), (int)sel);
-        uint32_t c = lane < per ? h[per * sel + ((sel * per) >> 6 << 2) + lane] : 0u;
-        if (pass == 1) c &= 0xFFFFu;
-        if (pass == 2) c >>= 16;
-        const uint32_t incl2 = wave_inclusive_sum(c);
-        const uint64_t holder2 = __builtin_amdgcn_ballot_w64(incl2 - c < rank && rank <= incl2);
-        const uint32_t sel2 = (uint32_t)__builtin_ctzll(holder2 | (1ull << 63));
-        rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl2 - c), (int)sel2);
-        prefix = (prefix << bits) | (sel * per + sel2);
+        uint32_t sel2 = 0;
+#pragma unroll
+        for (uint32_t k = 0; k + 1 < nb; ++k) {
+            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)c[k], (int)sel);
+            if (sel2 == k && rank > e) { rank -= e; sel2 = k + 1; }
+        }
+        if (lane == 0) { res[2 * pass] = sel * nb + sel2; res[2 * pass + 1] = rank; }
+        }
+        __syncthreads();
+        prefix = (prefix << bits) | res[2 * pass];
+        rank = res[2 * pass + 1];
     }
     return prefix;
 }
@@ -317,7 +339,7 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     uint32_t key[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) key[j] = (TAIL && !ok[j]) ? kInfBits : f2u(vh[j]);
-    const uint32_t xp_bits = select_rank<8>(key, rank, lane, work);
+    const uint32_t xp_bits = select_rank<8>(key, rank, lane, wave, work, xch + 8);
 
     // ---- encoder constants (every 16 lanes for themselves), codes, the wavefront's words
     const uint32_t lig = lane & 15u, gshift = lane & 16u;
@@ -582,7 +604,7 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
     uint32_t key[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) key[j] = f2u(vh[j]);
-    const uint32_t xp_bits = select_rank<16>(key, a.rank_full, lane, work);
+    const uint32_t xp_bits = select_rank<16>(key, a.rank_full, lane, wave, work, xch + 8);
 
     // ---- encoder constants (every 16 lanes for themselves), codes, the wavefront's words
     const uint32_t lig = lane & 15u, gshift = lane & 16u;
@@ -639,14 +661,19 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
 }
 
 // One workgroup of two wavefronts per full block of 2048 elements.
+// (Registers: the plain step with bf16 gradients fits five wavefronts per SIMD without spilling,
+// except with two ten-to-a-word streams; LDS allows five for every format.)
+template <int BM, int BV, bool BF16, bool EXT>
+constexpr int big_wide_waves() { return (BF16 && !EXT && !(BM == 3 && BV == 3)) ? kWideWaves + 1 : kWideWaves; }
+
 template <int BM, int BV, bool BF16, bool MDE, bool EXT>
-__global__ __launch_bounds__(kWideBigWaves * 64, kWideWaves)
+__global__ __launch_bounds__(kWideBigWaves * 64, (big_wide_waves<BM, BV, BF16, EXT>()))
 void big_wide_kernel(const StepArgs a)
 {
     constexpr int kDeWords = (MDE && BM >= 3) ? 4 * DeBuckets<BM>::N : 16;
     __shared__ __attribute__((aligned(64))) uint32_t lds_work[BigLayout::kWork];
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWideBigWaves * WideBigLayout::kSlab];
-    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[4];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[16];   // block maxima; bin and rank of every pass
     __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
     load_de_table<BM, MDE, kDeWords>(lds_de);
     const uint32_t lane = threadIdx.x & 63u;
@@ -663,7 +690,7 @@ void big_kernel(const StepArgs a)
     constexpr int kDeWords = (MDE && BM >= 3) ? 4 * DeBuckets<BM>::N : 16;
     __shared__ __attribute__((aligned(64))) uint32_t lds_work[BigLayout::kWork];
     __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kBigWaves * BigLayout::kSlab];
-    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[8];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[16];   // block maxima; bin and rank of every pass
     __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
     load_de_table<BM, MDE, kDeWords>(lds_de);
     const uint32_t lane = threadIdx.x & 63u;

@@ -474,6 +474,41 @@ def test_block_2048_config5_shape_ten_steps(so, gpu):
     note(f"block 2048, config-5 format, 2.1 M elements x 10 free-running steps: {flips} flips, {tainted} blocks diverged")
 
 
+@pytest.mark.parametrize("B,bm,bv", ((2048, 2, 3), (2048, 4, 2), (128, 2, 3)))
+def test_trained_state_with_clustered_second_moments(so, gpu, B, bm, bv):
+    """After some hundred updates the second moments of a block sit in a few tight clusters (beta2
+    times one of the 2^b decoded levels, plus a small fresh term): most keys of the quantile
+    selection then share their leading bits, the case the histograms of the large-block kernels
+    are laid out for.  300 steps on the GPU alone, then three steps compared with the oracle,
+    each starting from the GPU's own state."""
+    import torch
+    from paper_2505_00347_amd import synth
+    from parity_common import DeviceView
+    n = 40 * 2048 + 1283
+    oc, gc = make_cfgs(so, gpu, bm, bv, B, True)
+    side = GpuSide(gpu, n, gc)
+    side.p = dev(synth.make_params(n))
+    grads = [grads_for("normal_outliers", n, 1e-4, 5000 + k, True) for k in range(8)]
+    for step in range(1, 301):
+        side.step(grads[step % 8][1], step)
+    view = DeviceView.of(side.p, side.state)
+    flips = 0
+    for step in range(301, 304):
+        torch.cuda.synchronize()
+        p = side.p.cpu().numpy()
+        st = view.to_host_state(so, oc)
+        vc = so.unpack(st.v_words, n, bv)
+        g, g_dev = grads[step % 8]
+        side.step(g_dev, step)
+        p_before = p.astype(np.float64)
+        margin = so.step_packed(p, g, st, step, oc, want_margin=True, threads=8)
+        flips += compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr, p_before=p_before)
+    assert flips <= flip_budget(3 * n)
+    # the premise: the codes of the trained state use the levels of a block unevenly
+    top = np.bincount(vc[:2048], minlength=1 << bv).max()
+    assert top > 2 * 2048 // (1 << bv), "the trained state is not clustered"
+
+
 def test_block_2048_is_a_flat_buffer_format(gpu):
     """The multi-tensor launch has no kernels for blocks of 2048."""
     import ctypes as C
