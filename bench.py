@@ -340,7 +340,7 @@ def main():
 
     # the kernel that takes the time (the library picks it from the format, the size and the launch)
     if w.block_size == 2048:
-        kernel_name = "solo::big_wide_kernel"
+        kernel_name = "solo::multi_big_wide_kernel" if args.launch == "multi" else "solo::big_wide_kernel"
     elif args.launch == "multi":
         kernel_name = "solo::multi_chunk_kernel" if (w.grad_dtype == "fp32" and w.m_codebook == "linear") else "solo::multi_kernel"
     else:

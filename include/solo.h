@@ -77,8 +77,7 @@ typedef struct solo_config {
     uint32_t bits_m;       /* 2, 3 or 4: signed linear or dynamic-exponent codes (App. A) */
     uint32_t bits_v;       /* 2, 3 or 4: logarithmic codes (Sec. 3.2.2)                */
     uint32_t block_size;   /* 64, 128 or 2048 elements per block (Sec. 3.4 uses 128;   */
-                           /* 2048 is the large-block setting of Sec. 4.2, flat        */
-                           /* buffers only: not in solo_adamw_step_multi)              */
+                           /* 2048 is the large-block setting of Sec. 4.2)             */
     uint32_t grad_dtype;   /* SOLO_GRAD_FP32 or SOLO_GRAD_BF16                         */
     float lr;              /* learning rate                                            */
     float beta1;           /* momentum of the signed EMA, in [0,1); use the precision- */
@@ -208,8 +207,7 @@ typedef struct solo_tensor {
  * is the 2560 or 5120 elements one wavefront of that format's kernel owns, the ragged end of a
  * tensor counts one unit per 512 elements; with fp32 gradients and the linear codebook a unit is
  * 2560 elements or a tensor's shorter end, shared by five wavefronts); 0 if cfg is invalid.  At
- * most 2^24 tensors per table.  Block sizes 64 and 128 only (0 for 2048; the table build and the
- * step return SOLO_E_UNSUPPORTED). */
+ * most 2^24 tensors per table.  With blocks of 2048 elements a unit is one block. */
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg);
 
 /* Bytes of the table for `count` tensors and `units` units. */
@@ -219,6 +217,7 @@ size_t solo_multi_table_bytes(uint32_t count, uint64_t units);
  * array of descriptors holding DEVICE pointers) and set *table_flags (SOLO_TABLE_*), which
  * solo_adamw_step_multi takes back.  Checks every pointer's alignment. */
 #define SOLO_TABLE_BF16_COPY 1u   /* some tensor has a bf16 copy to write */
+#define SOLO_TABLE_SHORT_BLOCK 2u /* blocks of 2048: some tensor ends in a shorter block (a second launch) */
 int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const solo_config *cfg,
                            void *table_host, size_t table_bytes, uint32_t *table_flags);
 

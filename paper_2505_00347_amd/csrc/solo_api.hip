@@ -38,6 +38,16 @@ template <> hipError_t launch_big<2, true>(uint32_t, bool, const StepArgs &, hip
 template <> hipError_t launch_big<3, true>(uint32_t, bool, const StepArgs &, hipStream_t);
 template <> hipError_t launch_big<4, true>(uint32_t, bool, const StepArgs &, hipStream_t);
 
+template <int BM, bool MDE>
+hipError_t launch_multi_big(uint32_t bits_v, bool bf16, const MultiArgs &args, uint32_t count, bool ragged,
+                            hipStream_t stream);
+template <> hipError_t launch_multi_big<2, false>(uint32_t, bool, const MultiArgs &, uint32_t, bool, hipStream_t);
+template <> hipError_t launch_multi_big<3, false>(uint32_t, bool, const MultiArgs &, uint32_t, bool, hipStream_t);
+template <> hipError_t launch_multi_big<4, false>(uint32_t, bool, const MultiArgs &, uint32_t, bool, hipStream_t);
+template <> hipError_t launch_multi_big<2, true>(uint32_t, bool, const MultiArgs &, uint32_t, bool, hipStream_t);
+template <> hipError_t launch_multi_big<3, true>(uint32_t, bool, const MultiArgs &, uint32_t, bool, hipStream_t);
+template <> hipError_t launch_multi_big<4, true>(uint32_t, bool, const MultiArgs &, uint32_t, bool, hipStream_t);
+
 constexpr uint32_t kLargeBlock = 2048;      // the large-block setting (one workgroup per block)
 
 static bool bits_ok(uint32_t b) { return b >= 2 && b <= 4; }
@@ -264,9 +274,13 @@ int solo_adamw_step_mp(float *param, uint16_t *param_bf16, const void *grad, con
 
 uint64_t solo_multi_units(const solo_tensor *tensors, uint32_t count, const solo_config *cfg)
 {
-    if (!tensors || !solo::config_ok(cfg) || cfg->block_size == solo::kLargeBlock) return 0;
+    if (!tensors || !solo::config_ok(cfg)) return 0;
     const bool mde = (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0;
     uint64_t units = 0;
+    if (cfg->block_size == solo::kLargeBlock) {                  // one unit per block
+        for (uint32_t k = 0; k < count; ++k) units += (tensors[k].n + solo::kLargeBlock - 1) / solo::kLargeBlock;
+        return units;
+    }
     if (solo::multi_chunked(cfg->grad_dtype == SOLO_GRAD_BF16, mde)) {
         for (uint32_t k = 0; k < count; ++k) units += (tensors[k].n + solo::kTileUnit - 1) / solo::kTileUnit;
         return units;
@@ -285,14 +299,15 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
                            void *table_host, size_t table_bytes, uint32_t *table_flags)
 {
     if (!solo::config_ok(cfg) || !tensors || !table_host || !table_flags || count == 0) return SOLO_E_INVALID;
-    if (cfg->block_size == solo::kLargeBlock) return SOLO_E_UNSUPPORTED;   // blocks of 2048: flat buffers only
     if (count > solo::kMapTensorMask) return SOLO_E_UNSUPPORTED;      // the map keeps the tensor index in 24 bits
     const uint64_t units = solo_multi_units(tensors, count, cfg);
     if (table_bytes < solo_multi_table_bytes(count, units)) return SOLO_E_INVALID;
     if (units > (1ull << 31)) return SOLO_E_UNSUPPORTED;
-    const uint64_t unit = (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
-                                                     (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
-    const bool chunked = solo::multi_chunked(cfg->grad_dtype == SOLO_GRAD_BF16,
+    const bool big = cfg->block_size == solo::kLargeBlock;
+    const uint64_t unit = big ? solo::kLargeBlock
+                              : (uint64_t)solo::unit_elems(cfg->bits_m, cfg->bits_v, cfg->block_size,
+                                                           (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
+    const bool chunked = !big && solo::multi_chunked(cfg->grad_dtype == SOLO_GRAD_BF16,
                                              (cfg->flags & SOLO_FLAG_M_DYNAMIC_EXPONENT) != 0);
     solo::TensorEntry *entries = static_cast<solo::TensorEntry *>(table_host);
     uint32_t *map = reinterpret_cast<uint32_t *>(static_cast<char *>(table_host) + solo::multi_map_offset(count));
@@ -316,8 +331,10 @@ int solo_multi_table_build(const solo_tensor *tensors, uint32_t count, const sol
         e.reserved = 0;
         // full units first, then the 512-element iterations of the ragged end, one entry each
         // (chunked formats: one entry per 2560-element unit, the shorter last one included)
+        // (blocks of 2048: one entry per full block, then one flagged entry for a shorter last block)
         const uint64_t nf = chunked ? (t.n + solo::kTileUnit - 1) / solo::kTileUnit : solo::multi_full_units(t.n, unit);
-        const uint64_t nc = chunked ? 0 : solo::multi_ragged_chunks(t.n, unit);
+        const uint64_t nc = chunked ? 0 : big ? (t.n % unit ? 1 : 0) : solo::multi_ragged_chunks(t.n, unit);
+        if (big && nc) flags |= SOLO_TABLE_SHORT_BLOCK;
         for (uint64_t u = 0; u < nf; ++u) map[unit0 + u] = k;
         for (uint64_t c = 0; c < nc; ++c) map[unit0 + nf + c] = k | ((uint32_t)c << solo::kMapChunkShift) | solo::kMapRagged;
         unit0 += nf + nc;
@@ -331,7 +348,6 @@ int solo_adamw_step_multi(const void *table_device, uint32_t count, uint64_t uni
                           const float *grad_scale, uint64_t step, const solo_config *cfg, void *stream)
 {
     if (!solo::config_ok(cfg) || step == 0) return SOLO_E_INVALID;
-    if (cfg->block_size == solo::kLargeBlock) return SOLO_E_UNSUPPORTED;
     if (units == 0) return SOLO_OK;
     if (count == 0 || !solo::aligned(table_device, 16) || (grad_scale && !solo::aligned(grad_scale, 4)))
         return SOLO_E_INVALID;
@@ -351,6 +367,19 @@ int solo_adamw_step_multi(const void *table_device, uint32_t count, uint64_t uni
     ma.groups_per_xcd = ((slots + solo::kWaves - 1) / solo::kWaves + solo::kXcds - 1) / solo::kXcds;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
+    if (cfg->block_size == solo::kLargeBlock) {
+        const bool ragged = (table_flags & SOLO_TABLE_SHORT_BLOCK) != 0;
+        switch (cfg->bits_m) {
+        case 2: e = mde ? solo::launch_multi_big<2, true>(cfg->bits_v, bf16, ma, count, ragged, s)
+                        : solo::launch_multi_big<2, false>(cfg->bits_v, bf16, ma, count, ragged, s); break;
+        case 3: e = mde ? solo::launch_multi_big<3, true>(cfg->bits_v, bf16, ma, count, ragged, s)
+                        : solo::launch_multi_big<3, false>(cfg->bits_v, bf16, ma, count, ragged, s); break;
+        case 4: e = mde ? solo::launch_multi_big<4, true>(cfg->bits_v, bf16, ma, count, ragged, s)
+                        : solo::launch_multi_big<4, false>(cfg->bits_v, bf16, ma, count, ragged, s); break;
+        default: return SOLO_E_UNSUPPORTED;
+        }
+        return e == hipSuccess ? SOLO_OK : SOLO_E_HIP;
+    }
     switch (cfg->bits_m) {
     case 2: e = mde ? solo::launch_multi<2, true>(cfg->bits_v, cfg->block_size, bf16, ma, s)
                     : solo::launch_multi<2, false>(cfg->bits_v, cfg->block_size, bf16, ma, s); break;

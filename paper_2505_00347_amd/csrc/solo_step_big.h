@@ -706,6 +706,94 @@ void big_kernel(const StepArgs a)
     step_block_big<BM, BV, BF16, MDE, true, EXT>(a, blk, lane, wave, slab, lds_work, lds_xch, lds_de);
 }
 
+// The step over many tensors in one launch, blocks of 2048 elements.  The map of the table holds
+// one entry per block of every tensor (the tensor's index; a shorter last block is flagged).  A
+// workgroup of multi_big_wide_kernel takes one entry and, unless it is flagged, runs the full
+// block; workgroup k of multi_big_tail_kernel runs the shorter last block of tensor k, if it has
+// one.  Blocks never span tensors.
+__device__ __forceinline__ StepArgs tensor_args(const MultiArgs &ma, const TensorEntry &e)
+{
+    StepArgs a = ma.common;
+    a.param = e.param; a.param_bf16 = e.param_bf16; a.grad = e.grad;
+    a.m_words = e.m_words; a.m_scale = e.m_scale;
+    a.v_words = e.v_words; a.v_scale = e.v_scale; a.v_base = e.v_base;
+    a.n = e.n; a.index_offset = e.index_offset;
+    return a;
+}
+
+template <int BM, int BV, bool BF16, bool MDE, bool EXT>
+__global__ __launch_bounds__(kWideBigWaves * 64, (big_wide_waves<BM, BV, BF16, EXT>()))
+void multi_big_wide_kernel(const MultiArgs ma)
+{
+    constexpr int kDeWords = (MDE && BM >= 3) ? 4 * DeBuckets<BM>::N : 16;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_work[BigLayout::kWork];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kWideBigWaves * WideBigLayout::kSlab];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[16];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
+    const uint64_t unit = blockIdx.x;
+    if (unit >= ma.total_units) return;
+    const uint32_t me = ma.unit_map[unit];                      // uniform: scalar loads
+    if (me & kMapRagged) return;                                // (the whole workgroup: no barrier has been reached)
+    load_de_table<BM, MDE, kDeWords>(lds_de);
+    const TensorEntry &e = ma.entries[me & kMapTensorMask];
+    const StepArgs a = tensor_args(ma, e);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    step_block_wide<BM, BV, BF16, MDE, EXT>(a, unit - e.unit0, lane, wave, lds_slab + wave * WideBigLayout::kSlab,
+                                            lds_work, lds_xch, lds_de);
+}
+
+template <int BM, int BV, bool BF16, bool MDE>
+__global__ __launch_bounds__(kBigWaves * 64, SOLO_MIN_WAVES)
+void multi_big_tail_kernel(const MultiArgs ma, const uint32_t count)
+{
+    constexpr int kDeWords = (MDE && BM >= 3) ? 4 * DeBuckets<BM>::N : 16;
+    __shared__ __attribute__((aligned(64))) uint32_t lds_work[BigLayout::kWork];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_slab[kBigWaves * BigLayout::kSlab];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_xch[16];
+    __shared__ __attribute__((aligned(64))) uint32_t lds_de[kDeWords];
+    if (blockIdx.x >= count) return;
+    const TensorEntry &e = ma.entries[blockIdx.x];
+    if (e.n % kBigBlock == 0) return;                           // (the whole workgroup)
+    load_de_table<BM, MDE, kDeWords>(lds_de);
+    const StepArgs a = tensor_args(ma, e);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    step_block_big<BM, BV, BF16, MDE, true, true>(a, e.n / kBigBlock, lane, wave, lds_slab + wave * BigLayout::kSlab,
+                                                  lds_work, lds_xch, lds_de);
+}
+
+template <int BM, bool MDE>
+hipError_t launch_multi_big(uint32_t bits_v, bool bf16, const MultiArgs &args, uint32_t count, bool ragged,
+                            hipStream_t stream);
+
+template <int BM, bool MDE>
+hipError_t launch_multi_big_impl(uint32_t bits_v, bool bf16, const MultiArgs &args, uint32_t count, bool ragged,
+                                 hipStream_t stream)
+{
+    if (args.total_units == 0 || args.total_units > 0x7FFFFFFFull || count == 0) return hipErrorInvalidValue;
+    const StepArgs &c = args.common;
+    const bool ext = args.any_bf16_copy || c.grad_scale || c.belief || c.l2 != 0.0f;
+#define SOLO_LAUNCH(BV_, BF_, EXT_)                                                                 \
+    do {                                                                                            \
+        hipLaunchKernelGGL((multi_big_wide_kernel<BM, BV_, BF_, MDE, EXT_>), dim3((uint32_t)args.total_units), \
+                           dim3(kWideBigWaves * 64), 0, stream, args);                              \
+        if (ragged)                                                                                 \
+            hipLaunchKernelGGL((multi_big_tail_kernel<BM, BV_, BF_, MDE>), dim3(count),             \
+                               dim3(kBigWaves * 64), 0, stream, args, count);                       \
+    } while (0)
+#define SOLO_CASE(BV_)                                                                              \
+    if (bits_v == BV_) {                                                                            \
+        if (bf16) { if (ext) SOLO_LAUNCH(BV_, true, true); else SOLO_LAUNCH(BV_, true, false); }    \
+        else      { if (ext) SOLO_LAUNCH(BV_, false, true); else SOLO_LAUNCH(BV_, false, false); }  \
+        return hipGetLastError();                                                                   \
+    }
+    SOLO_CASE(2) SOLO_CASE(3) SOLO_CASE(4)
+#undef SOLO_CASE
+#undef SOLO_LAUNCH
+    return hipErrorInvalidValue;
+}
+
 template <int BM, bool MDE>
 hipError_t launch_big(uint32_t bits_v, bool bf16, const StepArgs &args, hipStream_t stream);
 

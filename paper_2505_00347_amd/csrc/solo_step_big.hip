@@ -17,4 +17,22 @@ hipError_t launch_big<4, false>(uint32_t bits_v, bool bf16, const StepArgs &args
 {
     return launch_big_impl<4, false>(bits_v, bf16, args, stream);
 }
+template <>
+hipError_t launch_multi_big<2, false>(uint32_t bits_v, bool bf16, const MultiArgs &args, uint32_t count, bool ragged,
+                                     hipStream_t stream)
+{
+    return launch_multi_big_impl<2, false>(bits_v, bf16, args, count, ragged, stream);
+}
+template <>
+hipError_t launch_multi_big<3, false>(uint32_t bits_v, bool bf16, const MultiArgs &args, uint32_t count, bool ragged,
+                                     hipStream_t stream)
+{
+    return launch_multi_big_impl<3, false>(bits_v, bf16, args, count, ragged, stream);
+}
+template <>
+hipError_t launch_multi_big<4, false>(uint32_t bits_v, bool bf16, const MultiArgs &args, uint32_t count, bool ragged,
+                                     hipStream_t stream)
+{
+    return launch_multi_big_impl<4, false>(bits_v, bf16, args, count, ragged, stream);
+}
 }  // namespace solo

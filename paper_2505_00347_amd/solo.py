@@ -19,6 +19,7 @@ SOLO_FLAG_STOCHASTIC = 1
 SOLO_FLAG_M_DYNAMIC_EXPONENT = 2
 SOLO_FLAG_ADABELIEF = 4
 SOLO_FLAG_COUPLED_DECAY = 8
+SOLO_TABLE_BF16_COPY, SOLO_TABLE_SHORT_BLOCK = 1, 2
 
 
 class solo_config(C.Structure):

@@ -154,8 +154,7 @@ def test_multi_tensor_table_layout(solo):
 
 def test_multi_table_of_a_chunked_format_and_large_blocks(solo):
     """With fp32 gradients and the linear codebook a table holds one entry per 2560-element unit
-    (the shorter end of a tensor included); blocks of 2048 elements have no multi-tensor launch
-    but all size queries."""
+    (the shorter end of a tensor included); with blocks of 2048 elements one entry per block."""
     import numpy as np
     cfg = solo.make_config(bits_m=2, bits_v=2, block_size=64, grad_dtype=solo.SOLO_GRAD_FP32)
     sizes = [1, 2559, 2560, 2561, 0, 7680, 12801]
@@ -175,9 +174,26 @@ def test_multi_table_of_a_chunked_format_and_large_blocks(solo):
     # the same tensors with bf16 gradients: super-tiles plus one entry per 512 elements of a ragged end
     cfg16 = solo.make_config(bits_m=2, bits_v=2, block_size=64, grad_dtype=solo.SOLO_GRAD_BF16)
     assert solo.solo_multi_units(arr, len(sizes), cfg16) != units
+    # blocks of 2048 elements: one entry per block, a shorter last block flagged (bit 31) and
+    # announced in the table's flags, since it takes a second launch
     big = solo.make_config(bits_m=2, bits_v=3, block_size=2048, grad_dtype=solo.SOLO_GRAD_BF16)
-    assert solo.solo_multi_units(arr, len(sizes), big) == 0
-    assert solo.solo_multi_table_build(arr, len(sizes), big, buf.ctypes.data, nbytes, check=False)[0] == solo.SOLO_E_UNSUPPORTED
+    want_units = [-(-n // 2048) for n in sizes]
+    units = solo.solo_multi_units(arr, len(sizes), big)
+    assert units == sum(want_units)
+    nbytes = solo.solo_multi_table_bytes(len(sizes), units)
+    buf = np.zeros(nbytes, np.uint8)
+    rc, flags = solo.solo_multi_table_build(arr, len(sizes), big, buf.ctypes.data, nbytes)
+    assert rc == solo.SOLO_OK and flags == solo.SOLO_TABLE_SHORT_BLOCK
+    want_map = []
+    for k, n in enumerate(sizes):
+        want_map += [k] * (n // 2048) + ([k | 0x80000000] if n % 2048 else [])
+    assert list(buf[96 * len(sizes):].view(np.uint32)) == want_map
+    for k in range(len(sizes)):
+        arr[k].n = 2048 * k
+    units = solo.solo_multi_units(arr, len(sizes), big)
+    assert units == sum(range(len(sizes)))
+    buf = np.zeros(solo.solo_multi_table_bytes(len(sizes), units), np.uint8)
+    assert solo.solo_multi_table_build(arr, len(sizes), big, buf.ctypes.data, buf.size) == (solo.SOLO_OK, 0)
     assert solo.solo_num_blocks(5000, 2048) == 3
     assert solo.solo_state_bytes(4096, big) == 4 * (256 + 410) + 12 * 2
 

@@ -509,18 +509,6 @@ def test_trained_state_with_clustered_second_moments(so, gpu, B, bm, bv):
     assert top > 2 * 2048 // (1 << bv), "the trained state is not clustered"
 
 
-def test_block_2048_is_a_flat_buffer_format(gpu):
-    """The multi-tensor launch has no kernels for blocks of 2048."""
-    import ctypes as C
-    solo = gpu
-    cfg = solo.make_config(bits_m=2, bits_v=3, block_size=2048)
-    arr = (solo.solo_tensor * 1)()
-    assert solo.solo_multi_units(arr, 1, cfg) == 0
-    buf = (C.c_uint8 * 256)()
-    assert solo.solo_multi_table_build(arr, 1, cfg, buf, 256, check=False)[0] == solo.SOLO_E_UNSUPPORTED
-    assert solo.solo_adamw_step_multi(16, 1, 1, 0, None, 1, cfg, check=False) == solo.SOLO_E_UNSUPPORTED
-
-
 # ------------------------------------------------------- many tensors in one launch
 
 @pytest.mark.parametrize("bm,bv,B,bf16,de,optimizer,extras", [(2, 3, 128, True, False, "adamw", False),
@@ -528,7 +516,10 @@ def test_block_2048_is_a_flat_buffer_format(gpu):
                                                              (4, 2, 128, True, True, "adamw", True),
                                                              (3, 3, 64, False, False, "adabelief", True),
                                                              (2, 2, 64, False, True, "adamw", True),
-                                                             (4, 4, 128, False, False, "adam_l2", False)])
+                                                             (4, 4, 128, False, False, "adam_l2", False),
+                                                             (2, 3, 2048, True, False, "adamw", False),
+                                                             (4, 2, 2048, True, True, "adabelief", True),
+                                                             (3, 3, 2048, False, False, "adam_l2", True)])
 def test_multi_tensor_step_equals_per_tensor_steps(so, gpu, bm, bv, B, bf16, de, optimizer, extras):
     """solo_adamw_step_multi over tensors of awkward sizes (empty, smaller than a block, one
     element past a unit, several units) against the oracle run on every tensor alone with the
