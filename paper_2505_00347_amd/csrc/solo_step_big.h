@@ -119,32 +119,32 @@ __device__ __forceinline__ uint32_t select_rank(const uint32_t (&key)[NK], uint3
         // inside it in LDS for the others: a second barrier costs less than every wavefront
         // summing the whole histogram for itself.
         if (wave == (uint32_t)(pass & 1)) {
-        // this lane's bins: 4 of 256 (2 of 128), `per` words from word per * lane, behind the pads in front of it
-        const uint32_t nb = (1u << bits) / 64u;                                 // bins per lane
-        const uint32_t per = nb * R;                                            // words per lane: 32, 32, 16, 8
-        const uint32_t row = per * lane + (((per * lane) >> 6) << 2);
-        uint32_t c[4] = {0, 0, 0, 0};
+            // this lane's bins: 4 of 256 (2 of 128), `per` words from word per * lane, behind the pads in front of it
+            const uint32_t nb = (1u << bits) / 64u;                                 // bins per lane
+            const uint32_t per = nb * R;                                            // words per lane: 32, 32, 16, 8
+            const uint32_t row = per * lane + (((per * lane) >> 6) << 2);
+            uint32_t c[4] = {0, 0, 0, 0};
 #pragma unroll
-        for (uint32_t k = 0; k < nb; ++k) {
+            for (uint32_t k = 0; k < nb; ++k) {
 #pragma unroll
-            for (uint32_t i = 0; i < R / 4u; ++i) {
-                const uint4 c4 = *reinterpret_cast<const uint4 *>(h + row + k * R + 4u * i);
-                c[k] += (c4.x + c4.y) + (c4.z + c4.w);
+                for (uint32_t i = 0; i < R / 4u; ++i) {
+                    const uint4 c4 = *reinterpret_cast<const uint4 *>(h + row + k * R + 4u * i);
+                    c[k] += (c4.x + c4.y) + (c4.z + c4.w);
+                }
+                c[k] = (pass & 1) ? c[k] >> 16 : c[k] & 0xFFFFu;
             }
-            c[k] = (pass & 1) ? c[k] >> 16 : c[k] & 0xFFFFu;
-        }
-        const uint32_t s = (c[0] + c[1]) + (c[2] + c[3]);
-        const uint32_t incl = wave_inclusive_sum(s);
-        const uint64_t holder = __builtin_amdgcn_ballot_w64(incl - s < rank && rank <= incl);   // one lane
-        const uint32_t sel = (uint32_t)__builtin_ctzll(holder | (1ull << 63));
-        rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl - s), (int)sel);
-        uint32_t sel2 = 0;
+            const uint32_t s = (c[0] + c[1]) + (c[2] + c[3]);
+            const uint32_t incl = wave_inclusive_sum(s);
+            const uint64_t holder = __builtin_amdgcn_ballot_w64(incl - s < rank && rank <= incl);   // one lane
+            const uint32_t sel = (uint32_t)__builtin_ctzll(holder | (1ull << 63));
+            rank -= (uint32_t)__builtin_amdgcn_readlane((int)(incl - s), (int)sel);
+            uint32_t sel2 = 0;
 #pragma unroll
-        for (uint32_t k = 0; k + 1 < nb; ++k) {
-            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)c[k], (int)sel);
-            if (sel2 == k && rank > e) { rank -= e; sel2 = k + 1; }
-        }
-        if (lane == 0) { res[2 * pass] = sel * nb + sel2; res[2 * pass + 1] = rank; }
+            for (uint32_t k = 0; k + 1 < nb; ++k) {
+                const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)c[k], (int)sel);
+                if (sel2 == k && rank > e) { rank -= e; sel2 = k + 1; }
+            }
+            if (lane == 0) { res[2 * pass] = sel * nb + sel2; res[2 * pass + 1] = rank; }
         }
         __syncthreads();
         prefix = (prefix << bits) | res[2 * pass];
