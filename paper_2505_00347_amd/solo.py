@@ -62,6 +62,11 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with "
                               "`python -m paper_2505_00347_amd.build` (needs hipcc)")
+        # torch first: the wheel brings a HIP runtime of its own and exports it to the process.
+        # Loaded after it, libsolo binds to that runtime, the one the tensors and streams of the
+        # callers belong to; loaded before it, libsolo would bind to the system's copy, and every
+        # launch on a torch stream would fail.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, u32, u64, cfgp = C.c_void_p, C.c_uint32, C.c_uint64, C.POINTER(solo_config)
         L.solo_code_words.restype = C.c_size_t; L.solo_code_words.argtypes = [u64, u32]

@@ -3,6 +3,7 @@ include/solo.h declares, and its pure host helpers agree with the paper's printe
 import ctypes
 import os
 import re
+import sys
 
 import pytest
 
@@ -196,6 +197,16 @@ def test_multi_table_of_a_chunked_format_and_large_blocks(solo):
     assert solo.solo_multi_table_build(arr, len(sizes), big, buf.ctypes.data, buf.size) == (solo.SOLO_OK, 0)
     assert solo.solo_num_blocks(5000, 2048) == 3
     assert solo.solo_state_bytes(4096, big) == 4 * (256 + 410) + 12 * 2
+
+
+def test_binding_loads_torch_before_the_library():
+    """The torch wheel carries a HIP runtime of its own; libsolo must be loaded after it so that
+    both use the same one (a process that loaded libsolo first failed every launch on a torch
+    stream).  The binding therefore imports torch itself before it opens the library."""
+    import subprocess
+    code = ("import sys; from paper_2505_00347_amd import solo; assert 'torch' not in sys.modules; "
+            "solo.lib(); assert 'torch' in sys.modules")
+    subprocess.run([sys.executable, "-c", code], cwd=ROOT, check=True, timeout=300)
 
 
 def test_product_does_not_import_the_oracle():

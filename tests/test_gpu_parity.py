@@ -597,16 +597,14 @@ def test_multi_tensor_table_rejects_bad_descriptors(gpu):
 
 # ------------------------------------------------------------------- randomized sweep
 
-@pytest.mark.parametrize("seed", (1, 2, 3))
-def test_randomized_sweep(so, gpu, seed):
-    """Forty seeded random combinations per seed of format, block size, codebook, gradient type and
-    distribution, optimizer, quantile, size (ragged ends included), hyper-parameters, xi on/off,
-    stream position and extras, with gradient magnitudes from 1e-15 to 1e6: three steps each from
-    equal states.  (Sweeps of this kind are what found the nearly-constant-block regime.)"""
+def random_cases(so, gpu, seed, blocks, cases):
+    """Seeded random combinations of format, block size, codebook, gradient type and distribution,
+    optimizer, quantile, size (ragged ends included), hyper-parameters, xi on/off, stream position
+    and extras, with gradient magnitudes from 1e-15 to 1e6: three steps each from equal states."""
     rng = np.random.default_rng(seed)
-    for c in range(40):
+    for c in range(cases):
         bm, bv = int(rng.integers(2, 5)), int(rng.integers(2, 5))
-        B = int(rng.choice([64, 128]))
+        B = int(rng.choice(blocks))
         de, bf16 = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
         opt = str(rng.choice(["adamw", "adamw", "adam_l2", "adabelief"]))
         n = int(rng.choice([rng.integers(1, 3000), rng.integers(3000, 40000),
@@ -627,6 +625,19 @@ def test_randomized_sweep(so, gpu, seed):
                                seed0=int(rng.integers(0, 10 ** 6)), **kw)
         except AssertionError as e:
             raise AssertionError(f"case {c}: n={n} m{bm} v{bv} B{B} bf16={bf16} {kind} std={std:.3g} {kw}: {e}") from e
+
+
+@pytest.mark.parametrize("seed", (1, 2, 3))
+def test_randomized_sweep(so, gpu, seed):
+    """Forty random combinations per seed with blocks of 64 and 128 elements.  (Sweeps of this kind
+    are what found the nearly-constant-block regime.)"""
+    random_cases(so, gpu, seed, [64, 128], 40)
+
+
+@pytest.mark.parametrize("seed", (11, 12))
+def test_randomized_sweep_block_2048(so, gpu, seed):
+    """Thirty random combinations per seed with blocks of 2048 elements."""
+    random_cases(so, gpu, seed, [2048, 2048], 30)
 
 
 # ---------------------------------- the benchmark's workload at its full size, sampled
