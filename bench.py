@@ -11,6 +11,7 @@ Prints ONE JSON line: updated parameters per second, the HBM roofline of the ste
 oracle timed on the host cores of this machine on a bounded sample of the same workload.
 """
 import argparse
+import contextlib
 import json
 import os
 import sys
@@ -234,12 +235,13 @@ def main():
                 self.extras = {"param_bf16": torch.empty(n, dtype=torch.bfloat16, device="cuda"),
                                "grad_scale": torch.tensor([0.5], dtype=torch.float32, device="cuda")}
             self.step = 0
-            spacer = None
-            if apart and n >= (1 << 28):         # (smaller buffers run the kernels that show no such effect)
-                used = 4 * n + 2 * (2 if w.grad_dtype == "bf16" else 4) * n + (2 * n if mp else 0)
-                room = torch.cuda.mem_get_info()[0] - (8 << 30)
-                if 0 < (96 << 30) - used < room:
-                    spacer = torch.empty((96 << 30) - used, dtype=torch.uint8, device="cuda")
+            # (smaller buffers run the kernels that show no placement effect)
+            used = 4 * n + 2 * (2 if w.grad_dtype == "bf16" else 4) * n + (2 * n if mp else 0)
+            with (solo.state_region(used) if apart and n >= (1 << 28) else contextlib.nullcontext()):
+                self.allocate_state()
+            torch.cuda.synchronize()
+
+        def allocate_state(self):
             if args.launch == "flat":
                 self.state = solo.SoloState(n, cfg)
             else:
@@ -255,10 +257,6 @@ def main():
                 if args.launch == "multi":
                     self.tables = [solo.SoloMultiTable([(t[0], t[1][k], t[2], t[3]) for t in self.tensors], cfg)
                                    for k in (0, 1)]
-            if spacer is not None:
-                del spacer
-                torch.cuda.empty_cache()         # the spacer goes back to the driver, not into torch's cache
-            torch.cuda.synchronize()
 
         def one_step(self):
             self.step += 1

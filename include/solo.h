@@ -24,6 +24,9 @@
  *     the call returns at once.
  *   - Return value: SOLO_OK (0) or a negative error code; nothing is enqueued
  *     when an error is returned.  n == 0 is a successful no-op.
+ *   - The library uses the HIP runtime it finds in the process.  A process
+ *     that brings one of its own (a PyTorch wheel does) loads that first, so
+ *     that the streams it passes and the launches belong to the same runtime.
  *
  * State layout for n elements, block size B, nb = ceil(n / B) blocks
  *   m_codes  uint32[solo_code_words(n, bits_m)]   element i lives in word
@@ -147,7 +150,7 @@ int solo_state_init(uint32_t *m_codes, float *m_scale,
  * not matter.  A process that starts on an idle GPU receives physical memory in allocation order:
  * a long-lived optimizer does well to allocate its state so that it does not end up in the
  * third of HBM that holds the parameters (python -m paper_2505_00347_amd.hbm_regions measures
- * the effect; bench.py shows one way to do it). */
+ * the effect; state_region of the Python binding does it, and bench.py allocates that way). */
 int solo_adamw_step(float *param, const void *grad,
                     uint32_t *m_codes, float *m_scale,
                     uint32_t *v_codes, float *v_scale, float *v_base,
