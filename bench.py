@@ -25,7 +25,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X: 8 TB/s HBM3E
 
 # HBM bytes per launch of the step kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a plain copy of known size (see profiles/).
-MEASURED_TRAFFIC = {"c5_llama7b_2bit_3bit": 77.408e9}   # profiles/step_kernel_c5_llama7b_traffic.txt
+MEASURED_TRAFFIC = {"c5_llama7b_2bit_3bit": 77.408e9,    # profiles/step_kernel_c5_llama7b_traffic.txt
+                    "c5_llama7b_block2048": 77.78e9}     # profiles/big_wide_kernel_c5_block2048.txt
 
 
 def bytes_per_param(w):
