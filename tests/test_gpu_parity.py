@@ -642,13 +642,15 @@ def test_randomized_sweep_block_2048(so, gpu, seed):
 
 # ---------------------------------- the benchmark's workload at its full size, sampled
 
-@pytest.mark.parametrize("name,variant", [("c5_llama7b_2bit_3bit", "plain"), ("paper_4_2bit_llama7b", "mp")])
+@pytest.mark.parametrize("name,variant", [("c5_llama7b_2bit_3bit", "plain"), ("paper_4_2bit_llama7b", "mp"),
+                                          ("c5_llama7b_block2048", "plain")])
 def test_full_size_7b_workload_sampled_tiles(so, gpu, name, variant):
     """The LLaMA-7B-shaped workloads exactly as bench.py launches them (6,738,415,616 elements,
     one call): the metric's format, and the paper's own 4/2-bit format (dynamic-exponent m)
     through solo_adamw_step_mp with the bf16 weight copy and a gradient scale.  The oracle cannot
     run 6.7e9 elements in seconds, so the third step is checked on sampled 5120-element
-    super-tiles (first, last full, the ragged tail, tensor boundaries and random ones): inputs of
+    super-tiles (first, last full, the ragged tail, tensor boundaries and random ones; with blocks
+    of 2048 elements, slices of five blocks): inputs of
     those slices are copied out before the step, the oracle runs on each slice with the slice's
     global offset, and every output byte of the slice is compared.  Properties that hold at any
     size are checked on the whole buffer."""
@@ -679,7 +681,7 @@ def test_full_size_7b_workload_sampled_tiles(so, gpu, name, variant):
         state.step(p, g, step, **extras)
         del g
     g = bench.device_grads(torch, n, w.grad_kind, gstd, synth.seed_grad(w.config_id, 3), torch.bfloat16)
-    T = TILE
+    T = TILE if B != 2048 else 5 * 2048          # slices start on a block and on a word of both streams
     n_tiles = n // T
     rng = np.random.default_rng(0)
     tiles = {0, 1, n_tiles - 1, n_tiles}                         # n_tiles = the ragged tail
