@@ -300,8 +300,10 @@ def test_config5_full_size_slices_per_tensor_class(so, gpu):
 
 # --------------------------------------------------------------- exactly once, at full size
 
-def test_config5_full_size_every_tile_exactly_once(so, gpu):
-    """Whole-buffer properties of the metric's launch (6.7e9 elements, one call).  (1) From the
+@pytest.mark.parametrize("name", ("c5_llama7b_2bit_3bit", "c5_llama7b_block2048"))
+def test_config5_full_size_every_tile_exactly_once(so, gpu, name):
+    """Whole-buffer properties of the metric's launch (6.7e9 elements, one call; also with blocks
+    of 2048 elements, where a "tile" below is a run of five blocks).  (1) From the
     zero state under a constant gradient every block must land on the one state the oracle
     computes for a single block, and every parameter on p (1 - lr wd) - u with the one update u:
     a tile that is skipped, or stepped twice, shows.  (2) With random gradients, a step from a
@@ -313,13 +315,14 @@ def test_config5_full_size_every_tile_exactly_once(so, gpu):
     import bench
     from paper_2505_00347_amd import synth
     solo = gpu
-    w = synth.workload("c5_llama7b_2bit_3bit")
+    w = synth.workload(name)
     n = w.n
     free, _ = torch.cuda.mem_get_info()
     if free < 130 * 2 ** 30:
         pytest.skip("needs 130 GiB of free HBM")
     oc, gc = workload_cfgs(so, solo, w)
     B, cm, cv = w.block_size, 32 // w.bits_m, 32 // w.bits_v
+    tile, PIECE = (5120, 2560) if B != 2048 else (5 * 2048, 5 * 2048)   # whole blocks and whole words of both streams
     p = bench.device_params(torch, w, synth.SEED_PARAM)
     state = solo.SoloState(n, gc)
 
@@ -344,7 +347,7 @@ def test_config5_full_size_every_tile_exactly_once(so, gpu):
         err = (p[a:a + chunk].double() - want).abs()
         assert bool((err <= 1e-6 * want.abs() + 2e-6 * oc.lr).all()), f"constant-gradient update wrong in [{a}, {a + chunk})"
     del p0, g
-    progress("c5 exactly-once: constant gradient done")
+    progress(f"{name} exactly-once: constant gradient done")
 
     # (2) random gradients from a warmed-up state
     for step in (2, 3):
@@ -363,29 +366,29 @@ def test_config5_full_size_every_tile_exactly_once(so, gpu):
     state.step(p, g, 4)
     torch.cuda.synchronize()
     whole = [p.clone()] + [getattr(state, k).clone() for k in names]
-    nt = n // TILE
-    assert bool((whole[0][:nt * TILE].view(nt, TILE) != before[0][:nt * TILE].view(nt, TILE)).any(1).all()), \
+    nt = n // tile
+    assert bool((whole[0][:nt * tile].view(nt, tile) != before[0][:nt * tile].view(nt, tile)).any(1).all()), \
         "a tile's parameters did not change"
-    assert bool((whole[4][:nt * (TILE // B)].view(nt, -1) != before[4][:nt * (TILE // B)].view(nt, -1)).any(1).all()), \
+    assert bool((whole[4][:nt * (tile // B)].view(nt, -1) != before[4][:nt * (tile // B)].view(nt, -1)).any(1).all()), \
         "a tile's Delta_v did not change"
-    mch = (whole[1][:nt * (TILE // cm)].view(nt, -1) != before[1][:nt * (TILE // cm)].view(nt, -1)).any(1)
-    vch = (whole[3][:nt * (TILE // cv)].view(nt, -1) != before[3][:nt * (TILE // cv)].view(nt, -1)).any(1)
+    mch = (whole[1][:nt * (tile // cm)].view(nt, -1) != before[1][:nt * (tile // cm)].view(nt, -1)).any(1)
+    vch = (whole[3][:nt * (tile // cv)].view(nt, -1) != before[3][:nt * (tile // cv)].view(nt, -1)).any(1)
     assert bool((mch | vch).all()), "a tile's code words did not change"
-    progress("c5 exactly-once: every tile changed")
+    progress(f"{name} exactly-once: every tile changed")
     restore()
     state.step(p, g, 4)
     torch.cuda.synchronize()
     for t, ref in zip([p] + [getattr(state, k) for k in names], whole):
         assert torch.equal(t, ref), "the step is not reproducible"
-    progress("c5 exactly-once: reproducible")
+    progress(f"{name} exactly-once: reproducible")
     # the same step in unequal pieces
     restore()
     rng = np.random.default_rng(5)
-    units = n // 2560
+    units = n // PIECE
     cuts = sorted(set([0, units] + [int(x) for x in rng.integers(1, units, 12)] +
                       [int(x) for x in (units // 3 + np.array([1, 3, 4, 9, 12, 100, 1000, 5000]))]))
-    cuts = [2560 * x for x in cuts]
-    if n % 2560:
+    cuts = [PIECE * x for x in cuts]
+    if n % PIECE:
         cuts[-1] = n
     for a, b in zip(cuts[:-1], cuts[1:]):
         cfg = solo.make_config(w.bits_m, w.bits_v, B, solo.SOLO_GRAD_BF16, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
@@ -395,7 +398,7 @@ def test_config5_full_size_every_tile_exactly_once(so, gpu):
     torch.cuda.synchronize()
     for t, ref, k in zip([p] + [getattr(state, k) for k in names], whole, ("p",) + names):
         assert torch.equal(t, ref), f"{k}: the step in {len(cuts) - 1} pieces differs from the step of the whole buffer"
-    note(f"c5 at full size: constant-gradient closed form on all {n // B} blocks, every one of {nt} tiles changed, "
+    note(f"{name} at full size: constant-gradient closed form on all {n // B} blocks, every one of {nt} tiles changed, "
          f"step reproducible, and equal bit for bit to the same step in {len(cuts) - 1} pieces "
          f"(sizes {min(b - a for a, b in zip(cuts[:-1], cuts[1:]))} .. {max(b - a for a, b in zip(cuts[:-1], cuts[1:]))})")
 
