@@ -375,15 +375,17 @@ def test_runs_on_the_callers_stream(so, gpu):
     compare_step(so, oc, n, p, st, margin, side.fetch(), 1e-6, 2e-6 * oc.lr)
 
 
-def test_step_can_be_captured_in_a_hip_graph(so, gpu):
-    """The library allocates nothing, synchronises nothing and enqueues only kernels, so a step
-    can be recorded into a HIP graph.  The replayed step (same step number, inputs restored by
-    eager copies between the replays) must reproduce the eager step bit for bit, every time."""
+@pytest.mark.parametrize("B", (128, 2048))
+def test_step_can_be_captured_in_a_hip_graph(so, gpu, B):
+    """The library allocates nothing, synchronises nothing and enqueues only kernels (two for a
+    buffer with a ragged end), so a step can be recorded into a HIP graph.  The replayed step
+    (same step number, inputs restored by eager copies between the replays) must reproduce the
+    eager step bit for bit, every time."""
     import torch
     from paper_2505_00347_amd import synth
     solo = gpu
     n = 3 * TILE + 777
-    _, gc = make_cfgs(so, solo, 2, 3, 128, True)
+    _, gc = make_cfgs(so, solo, 2, 3, B, True)
     p0 = dev(synth.make_params(n))
     g_host, g = grads_for("normal", n, 1e-3, 4242, True)
     st = solo.SoloState(n, gc)
