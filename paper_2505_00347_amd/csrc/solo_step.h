@@ -838,6 +838,128 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
     v8 = (uint32_t)(av_lo - OFFV) | ((uint32_t)(av_hi - OFFV) << (4 * BV));
 }
 
+// ---- pieces shared by the tile functions and the large-block functions (solo_step_big.h)
+
+// A lane's 8 consecutive elements out of the coalesced layout they were loaded in, through the
+// wavefront's staging area: st_c = stage + lane + lane / 8 (coalesced slots st_c[0], st_c[72]),
+// st_l = stage + 2 lane + lane / 4 (the lane's own two vectors).  TAIL: loaded per lane already.
+template <bool BF16, bool TAIL>
+__device__ __forceinline__ void lane_layout8(const RawPG &raw, float4 *const st_c, float4 *const st_l,
+                                             float (&p)[8], float (&g)[8])
+{
+    float4 pa = raw.p0, pb = raw.p1;
+    uint4 ga = raw.g0, gb = raw.g1;
+    if (!TAIL) {                       // coalesced layout -> 8 consecutive elements per lane
+        st_c[0] = pa; st_c[72] = pb;
+        wave_lds_sync();
+        pa = st_l[0]; pb = st_l[1];
+        if (!BF16) {
+            wave_lds_sync();
+            st_c[0] = make_float4(u2f(ga.x), u2f(ga.y), u2f(ga.z), u2f(ga.w));
+            st_c[72] = make_float4(u2f(gb.x), u2f(gb.y), u2f(gb.z), u2f(gb.w));
+            wave_lds_sync();
+            const float4 t0 = st_l[0], t1 = st_l[1];
+            ga = make_uint4(f2u(t0.x), f2u(t0.y), f2u(t0.z), f2u(t0.w));
+            gb = make_uint4(f2u(t1.x), f2u(t1.y), f2u(t1.z), f2u(t1.w));
+        }
+    }
+    p[0] = pa.x; p[1] = pa.y; p[2] = pa.z; p[3] = pa.w;
+    p[4] = pb.x; p[5] = pb.y; p[6] = pb.z; p[7] = pb.w;
+    if (BF16) {
+        g[0] = u2f(ga.x << 16); g[1] = u2f(ga.x & 0xFFFF0000u);
+        g[2] = u2f(ga.y << 16); g[3] = u2f(ga.y & 0xFFFF0000u);
+        g[4] = u2f(ga.z << 16); g[5] = u2f(ga.z & 0xFFFF0000u);
+        g[6] = u2f(ga.w << 16); g[7] = u2f(ga.w & 0xFFFF0000u);
+    } else {
+        g[0] = u2f(ga.x); g[1] = u2f(ga.y); g[2] = u2f(ga.z); g[3] = u2f(ga.w);
+        g[4] = u2f(gb.x); g[5] = u2f(gb.y); g[6] = u2f(gb.z); g[7] = u2f(gb.w);
+    }
+}
+
+// Dequantize (table look-up: byte offset 4 * code, OR-ed into the aligned table base), both EMAs
+// and the parameter for a lane's N = 8 or 16 consecutive elements; mc8 / vc8: the packed old
+// codes of every run of 8.  VMAX: also the largest v^ (the callers that sort take it from the
+// sorted keys).  TAIL: elements that do not exist (`ok`) leave zeros in m^ and v^.
+// AdaBelief without a branch: d = g - kb * m^ is g itself when kb = 0 and fl(g - m^) when kb = 1
+// (one rounding either way), and eps_state = 0 leaves v^ unchanged.
+// Parameter: decoupled decay, bias-corrected Adam direction,
+// p <- p * decay - step_size * m^ / (sqrt(v^ / bc2) + eps), with step_size folded into the denominator.
+template <int N, int BM, int BV, bool EXT, bool TAIL, bool VMAX>
+__device__ __forceinline__ void ema_param(const StepArgs &a, const uint32_t tm_addr, const uint32_t tv_addr,
+                                          const uint32_t *mc8, const uint32_t *vc8, const bool *ok,
+                                          float (&p)[N], const float (&g)[N], float (&mh)[N], float (&vh)[N],
+                                          float &m_absmax, float &v_max)
+{
+    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;   // byte-index masks
+    float mt[N], vt[N];
+    if (N == 8) {                              // (the narrow code fetches all levels first)
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const uint32_t om = (j == 0) ? (mc8[0] << 2) : (mc8[0] >> (BM * j - 2));
+            const uint32_t ov = (j == 0) ? (vc8[0] << 2) : (vc8[0] >> (BV * j - 2));
+            mt[j] = lds_f32(tm_addr | (om & MIDX));
+            vt[j] = lds_f32(tv_addr | (ov & VIDX));
+        }
+    }
+    m_absmax = 0.0f;
+    v_max = 0.0f;
+    const float kb = a.belief ? 1.0f : 0.0f;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if (N != 8) {
+            const int r = j / 8, jj = j % 8;
+            const uint32_t om = (jj == 0) ? (mc8[r] << 2) : (mc8[r] >> (BM * jj - 2));
+            const uint32_t ov = (jj == 0) ? (vc8[r] << 2) : (vc8[r] >> (BV * jj - 2));
+            mt[j] = lds_f32(tm_addr | (om & MIDX));
+            vt[j] = lds_f32(tv_addr | (ov & VIDX));
+        }
+        mh[j] = __builtin_fmaf(a.beta1, mt[j], a.omb1 * g[j]);
+        if (EXT) {
+            const float d = __builtin_fmaf(-kb, mh[j], g[j]);
+            vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (d * d)) + a.eps_state;
+        } else {
+            vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (g[j] * g[j]));
+        }
+        const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
+        p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
+        if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
+        m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
+        if (VMAX) v_max = __builtin_fmaxf(v_max, vh[j]);
+    }
+}
+
+// The new parameters of a lane's 8 elements (and their bf16 copy, if asked for) back to the
+// coalesced layout and streamed out; chunk_e0: first element of the wavefront's 512, e0: of the lane.
+template <bool EXT, bool TAIL>
+__device__ __forceinline__ void store_params8(const StepArgs &a, const uint64_t chunk_e0, const uint64_t e0,
+                                              const uint32_t lane, const bool *ok, const float (&p)[8],
+                                              float4 *const st_c, float4 *const st_l)
+{
+    if (EXT && a.param_bf16) {                    // 16-bit copy of the new parameters, 16 bytes per lane
+        if (!TAIL) {
+            const u32x4_t h = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
+                             pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+            stream_store_u4(a.param_bf16 + e0, h);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (ok[j]) a.param_bf16[e0 + j] = (uint16_t)pack_bf16(p[j], 0.0f);
+        }
+    }
+    if (!TAIL) {                           // back to the coalesced layout, streamed out
+        wave_lds_sync();
+        st_l[0] = make_float4(p[0], p[1], p[2], p[3]);
+        st_l[1] = make_float4(p[4], p[5], p[6], p[7]);
+        wave_lds_sync();
+        float *pp = a.param + chunk_e0 + lane * 4u;
+        stream_store_f4(pp, st_c[0]);
+        stream_store_f4(pp + 256, st_c[72]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
+    }
+}
+
 // One super-tile of TILE elements, processed by the calling wavefront: the whole step for the
 // elements [tile * TILE, (tile + 1) * TILE) of the buffers in `a` (TAIL: clipped to a.n, with
 // bounds checks on every element).  `slab` is this wavefront's LDS, `lds_de` the workgroup's DE
@@ -868,8 +990,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1; // entries of a block's m level table (3, 7, 15; DE: 4, 8, 16)
     constexpr int MTS = Lay::MTS;                  // stride of the m tables
     constexpr uint32_t GMASK = (G == 16) ? 0xFFFFu : 0xFFu;
-    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;   // byte-index masks
-
     // A runaway column address (possible only with non-finite input) stays inside the slab.
     constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
     constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
@@ -1000,94 +1120,17 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
 
         // ---- dequantize (table look-up), EMA, parameter
         float p[8], g[8];
-        {
-            float4 pa = raw.p0, pb = raw.p1;
-            uint4 ga = raw.g0, gb = raw.g1;
-            if (!TAIL) {                       // coalesced layout -> 8 consecutive elements per lane
-                st_c[0] = pa; st_c[72] = pb;
-                wave_lds_sync();
-                pa = st_l[0]; pb = st_l[1];
-                if (!BF16) {
-                    wave_lds_sync();
-                    st_c[0] = make_float4(u2f(ga.x), u2f(ga.y), u2f(ga.z), u2f(ga.w));
-                    st_c[72] = make_float4(u2f(gb.x), u2f(gb.y), u2f(gb.z), u2f(gb.w));
-                    wave_lds_sync();
-                    const float4 t0 = st_l[0], t1 = st_l[1];
-                    ga = make_uint4(f2u(t0.x), f2u(t0.y), f2u(t0.z), f2u(t0.w));
-                    gb = make_uint4(f2u(t1.x), f2u(t1.y), f2u(t1.z), f2u(t1.w));
-                }
-            }
-            p[0] = pa.x; p[1] = pa.y; p[2] = pa.z; p[3] = pa.w;
-            p[4] = pb.x; p[5] = pb.y; p[6] = pb.z; p[7] = pb.w;
-            if (BF16) {
-                g[0] = u2f(ga.x << 16); g[1] = u2f(ga.x & 0xFFFF0000u);
-                g[2] = u2f(ga.y << 16); g[3] = u2f(ga.y & 0xFFFF0000u);
-                g[4] = u2f(ga.z << 16); g[5] = u2f(ga.z & 0xFFFF0000u);
-                g[6] = u2f(ga.w << 16); g[7] = u2f(ga.w & 0xFFFF0000u);
-            } else {
-                g[0] = u2f(ga.x); g[1] = u2f(ga.y); g[2] = u2f(ga.z); g[3] = u2f(ga.w);
-                g[4] = u2f(gb.x); g[5] = u2f(gb.y); g[6] = u2f(gb.z); g[7] = u2f(gb.w);
-            }
-        }
+        lane_layout8<BF16, TAIL>(raw, st_c, st_l, p, g);
         if (EXT) {                             // g <- fl(g * scale), then one fused g + l2 * p (l2 = 0: exact)
 #pragma unroll
             for (int j = 0; j < 8; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
         }
         // next iteration's parameters and gradients, a whole iteration ahead of their use
         if (it + 1 < it_end) raw = load_pg<BF16, TAIL>(a, tile_e0 + (uint32_t)(it + 1) * kIter, lane);
-        float mt[8], vt[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {       // byte offset 4 * code, OR-ed into the aligned table base
-            const uint32_t om = (j == 0) ? (mc8 << 2) : (mc8 >> (BM * j - 2));
-            const uint32_t ov = (j == 0) ? (vc8 << 2) : (vc8 >> (BV * j - 2));
-            mt[j] = lds_f32(tm_addr | (om & MIDX));
-            vt[j] = lds_f32(tv_addr | (ov & VIDX));
-        }
         float mh[8], vh[8];
-        float m_absmax = 0.0f, v_max = 0.0f;
-        // AdaBelief without a branch: d = g - kb * m^ is g itself when kb = 0 and fl(g - m^) when
-        // kb = 1 (one rounding either way), and eps_state = 0 leaves v^ unchanged
-        const float kb = a.belief ? 1.0f : 0.0f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            mh[j] = __builtin_fmaf(a.beta1, mt[j], a.omb1 * g[j]);
-            if (EXT) {
-                const float d = __builtin_fmaf(-kb, mh[j], g[j]);
-                vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (d * d)) + a.eps_state;
-            } else {
-                vh[j] = __builtin_fmaf(a.beta2, vt[j], a.omb2 * (g[j] * g[j]));
-            }
-            // parameter: decoupled decay, bias-corrected Adam direction
-            // p <- p * decay - step_size * m^ / (sqrt(v^ / bc2) + eps), with step_size folded into the denominator
-            const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
-            p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
-            if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
-            m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
-            if (TAIL) v_max = __builtin_fmaxf(v_max, vh[j]);     // (full tiles: the last sorted key below)
-        }
-        if (EXT && a.param_bf16) {                    // 16-bit copy of the new parameters, 16 bytes per lane
-            if (!TAIL) {
-                const u32x4_t h = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
-                                 pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-                stream_store_u4(a.param_bf16 + e0, h);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (ok[j]) a.param_bf16[e0 + j] = (uint16_t)pack_bf16(p[j], 0.0f);
-            }
-        }
-        if (!TAIL) {                           // back to the coalesced layout, streamed out
-            wave_lds_sync();
-            st_l[0] = make_float4(p[0], p[1], p[2], p[3]);
-            st_l[1] = make_float4(p[4], p[5], p[6], p[7]);
-            wave_lds_sync();
-            float *pp = a.param + (tile_e0 + (uint32_t)it * kIter) + lane * 4u;
-            stream_store_f4(pp, st_c[0]);
-            stream_store_f4(pp + 256, st_c[72]);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
-        }
+        float m_absmax, v_max;                 // (v_max of full tiles: the last sorted key below)
+        ema_param<8, BM, BV, EXT, TAIL, TAIL>(a, tm_addr, tv_addr, &mc8, &vc8, ok, p, g, mh, vh, m_absmax, v_max);
+        store_params8<EXT, TAIL>(a, tile_e0 + (uint32_t)it * kIter, e0, lane, ok, p, st_c, st_l);
 
         // ---- the lane's v^ sorted (non-negative floats order like their bit patterns); block maxima
         uint32_t key[8];
@@ -1228,6 +1271,89 @@ __device__ __forceinline__ RawPG16<BF16> load_pg16(const StepArgs &a, uint64_t c
     return r;
 }
 
+// The staging slots of a lane for the layout transposition of a 1024-element iteration, 16-byte
+// vectors.  Vector i of the chunk sits in slot i + i / 8 (one pad vector after every 8): eight
+// neighbouring lanes then cover all banks both on the coalesced side (i = lane + 64 k) and on the
+// lane's own side (fp32: i = 4 lane + c, slot 4 lane + lane / 2 + c; bf16: i = 2 lane + c,
+// slot 2 lane + lane / 4 + c).  288 vectors.
+struct Stage16 {
+    float4 *c4, *l4, *c2, *l2;     // c4[72 k], l4[c]: 32-bit elements; c2[72 k], l2[c]: 16-bit elements
+    __device__ __forceinline__ Stage16(float4 *stage, uint32_t lane)
+        : c4(stage + (lane + lane / 8u)), l4(stage + (4u * lane + lane / 2u)),
+          c2(stage + (lane + lane / 8u)), l2(stage + (2u * lane + lane / 4u)) {}
+};
+
+// A lane's 16 consecutive elements out of the coalesced layout they were loaded in.
+template <bool BF16>
+__device__ __forceinline__ void lane_layout16(const RawPG16<BF16> &raw, const Stage16 &st,
+                                              float (&p)[16], float (&g)[16])
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) st.c4[72 * k] = raw.p[k];
+    wave_lds_sync();                   // (also orders the level tables before their readers)
+    float4 t[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) t[c] = st.l4[c];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { p[4 * c] = t[c].x; p[4 * c + 1] = t[c].y; p[4 * c + 2] = t[c].z; p[4 * c + 3] = t[c].w; }
+    wave_lds_sync();
+    if (BF16) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            st.c2[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+        wave_lds_sync();
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const float4 x = st.l2[c];
+            const uint32_t w[4] = {f2u(x.x), f2u(x.y), f2u(x.z), f2u(x.w)};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                g[8 * c + 2 * i] = u2f(w[i] << 16);
+                g[8 * c + 2 * i + 1] = u2f(w[i] & 0xFFFF0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < (BF16 ? 2 : 4); ++k)
+            st.c4[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
+        wave_lds_sync();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float4 x = st.l4[c];
+            g[4 * c] = x.x; g[4 * c + 1] = x.y; g[4 * c + 2] = x.z; g[4 * c + 3] = x.w;
+        }
+    }
+}
+
+// The new parameters of a lane's 16 elements (and their bf16 copy, if asked for: 32 bytes per
+// lane, two vectors, first) back to the coalesced layout and streamed out; chunk_e0: first
+// element of the wavefront's 1024.
+template <bool EXT>
+__device__ __forceinline__ void store_params16(const StepArgs &a, const uint64_t chunk_e0, const uint32_t lane,
+                                               const float (&p)[16], const Stage16 &st)
+{
+    wave_lds_sync();
+    if (EXT && a.param_bf16) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t h0 = pack_bf16(p[8 * c], p[8 * c + 1]), h1 = pack_bf16(p[8 * c + 2], p[8 * c + 3]);
+            const uint32_t h2 = pack_bf16(p[8 * c + 4], p[8 * c + 5]), h3 = pack_bf16(p[8 * c + 6], p[8 * c + 7]);
+            st.l2[c] = make_float4(u2f(h0), u2f(h1), u2f(h2), u2f(h3));
+        }
+        wave_lds_sync();
+        uint16_t *hp = a.param_bf16 + chunk_e0 + lane * 8u;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) stream_store_f4(reinterpret_cast<float *>(hp + 512 * k), st.c2[72 * k]);
+        wave_lds_sync();
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) st.l4[c] = make_float4(p[4 * c], p[4 * c + 1], p[4 * c + 2], p[4 * c + 3]);
+    wave_lds_sync();
+    float *pp = a.param + chunk_e0 + lane * 4u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st.c4[72 * k]);
+}
+
 // The wide path: the same step as step_tile() for a full super-tile, with 16 consecutive
 // elements per lane and 1024 per iteration.  A block is held by 8 lanes (4 for B = 64), so the
 // work that is done once per lane and block (level tables, the division, the base, the hash,
@@ -1253,7 +1379,6 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
     constexpr int VT = K + 1;
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
     constexpr int MTS = Lay::MTS;
-    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
     constexpr int kOffCol = Lay::kOffCol, kOffImgM = Lay::kOffImgM, kOffImgV = Lay::kOffImgV;
     constexpr int kOffTv = Lay::kOffTv, kOffTm = Lay::kOffTm, kOffSc = Lay::kOffSc, kSlab = Lay::kSlab;
     constexpr bool kDeTable = Lay::kDeTable;
@@ -1267,16 +1392,8 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
 
     RawPG16<BF16> raw = load_pg16<BF16>(a, tile_e0, lane);
     const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;
-    // Layout transposition through LDS, 16-byte vectors.  Vector i of the chunk sits in slot
-    // i + i / 8 (one pad vector after every 8): eight neighbouring lanes then cover all banks both
-    // on the coalesced side (i = lane + 64 k) and on the lane's own side (fp32: i = 4 lane + c,
-    // slot 4 lane + lane / 2 + c; bf16: i = 2 lane + c, slot 2 lane + lane / 4 + c).
     static_assert(288 * 4 <= 64 * kColStride16, "staging must fit the column area");
-    float4 *const stage = reinterpret_cast<float4 *>(slab + kOffCol);
-    float4 *const st4_c = stage + (lane + lane / 8u);       // + 72 k
-    float4 *const st4_l = stage + (4u * lane + lane / 2u);  // + c
-    float4 *const st2_c = stage + (lane + lane / 8u);       // + 72 k
-    float4 *const st2_l = stage + (2u * lane + lane / 4u);  // + c
+    const Stage16 st(reinterpret_cast<float4 *>(slab + kOffCol), lane);
 
     // ---- stage the super-tile's state in LDS
     static_assert(kOffImgM % 4 == 0 && kOffImgV % 4 == 0, "128-bit staging");
@@ -1348,43 +1465,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
 
         // ---- coalesced layout -> 16 consecutive elements per lane
         float p[16], g[16];
-        {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) st4_c[72 * k] = raw.p[k];
-            wave_lds_sync();                   // (also orders the level tables before their readers)
-            float4 t[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) t[c] = st4_l[c];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) { p[4 * c] = t[c].x; p[4 * c + 1] = t[c].y; p[4 * c + 2] = t[c].z; p[4 * c + 3] = t[c].w; }
-            wave_lds_sync();
-            if (BF16) {
-#pragma unroll
-                for (int k = 0; k < 2; ++k)
-                    st2_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
-                wave_lds_sync();
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const float4 x = st2_l[c];
-                    const uint32_t w[4] = {f2u(x.x), f2u(x.y), f2u(x.z), f2u(x.w)};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        g[8 * c + 2 * i] = u2f(w[i] << 16);
-                        g[8 * c + 2 * i + 1] = u2f(w[i] & 0xFFFF0000u);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < (BF16 ? 2 : 4); ++k)
-                    st4_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
-                wave_lds_sync();
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float4 x = st4_l[c];
-                    g[4 * c] = x.x; g[4 * c + 1] = x.y; g[4 * c + 2] = x.z; g[4 * c + 3] = x.w;
-                }
-            }
-        }
+        lane_layout16<BF16>(raw, st, p, g);
         if (EXT) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
@@ -1392,51 +1473,11 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         // next iteration's parameters and gradients, a whole iteration ahead of their use
         if (it + 1 < kIters) raw = load_pg16<BF16>(a, tile_e0 + (uint32_t)(it + 1) * kIter16, lane);
 
-        // ---- dequantize (table look-up), EMA, parameter
+        // ---- dequantize (table look-up), EMA, parameter; new parameters streamed out
         float mh[16], vh[16];
-        float m_absmax = 0.0f;
-        const float kb = a.belief ? 1.0f : 0.0f;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int r = j / 8, jj = j % 8;
-            const uint32_t om = (jj == 0) ? (mc8[r] << 2) : (mc8[r] >> (BM * jj - 2));
-            const uint32_t ov = (jj == 0) ? (vc8[r] << 2) : (vc8[r] >> (BV * jj - 2));
-            const float mt = lds_f32(tm_addr | (om & MIDX));
-            const float vt = lds_f32(tv_addr | (ov & VIDX));
-            mh[j] = __builtin_fmaf(a.beta1, mt, a.omb1 * g[j]);
-            if (EXT) {
-                const float d = __builtin_fmaf(-kb, mh[j], g[j]);
-                vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (d * d)) + a.eps_state;
-            } else {
-                vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (g[j] * g[j]));
-            }
-            const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
-            p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
-            m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
-        }
-        // ---- new parameters back to the coalesced layout, streamed out
-        wave_lds_sync();
-        if (EXT && a.param_bf16) {               // 16-bit copy first: 32 bytes per lane, two vectors
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const uint32_t h0 = pack_bf16(p[8 * c], p[8 * c + 1]), h1 = pack_bf16(p[8 * c + 2], p[8 * c + 3]);
-                const uint32_t h2 = pack_bf16(p[8 * c + 4], p[8 * c + 5]), h3 = pack_bf16(p[8 * c + 6], p[8 * c + 7]);
-                st2_l[c] = make_float4(u2f(h0), u2f(h1), u2f(h2), u2f(h3));
-            }
-            wave_lds_sync();
-            uint16_t *hp = a.param_bf16 + (tile_e0 + (uint32_t)it * kIter16) + lane * 8u;
-#pragma unroll
-            for (int k = 0; k < 2; ++k) stream_store_f4(reinterpret_cast<float *>(hp + 512 * k), st2_c[72 * k]);
-            wave_lds_sync();
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) st4_l[c] = make_float4(p[4 * c], p[4 * c + 1], p[4 * c + 2], p[4 * c + 3]);
-        wave_lds_sync();
-        {
-            float *pp = a.param + (tile_e0 + (uint32_t)it * kIter16) + lane * 4u;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st4_c[72 * k]);
-        }
+        float m_absmax, v_unused;               // (the largest v^ is the lane's last sorted key below)
+        ema_param<16, BM, BV, EXT, false, false>(a, tm_addr, tv_addr, mc8, vc8, nullptr, p, g, mh, vh, m_absmax, v_unused);
+        store_params16<EXT>(a, tile_e0 + (uint32_t)it * kIter16, lane, p, st);
         wave_lds_sync();                        // the staging area becomes the column area
 
         // ---- the lane's v^ sorted (non-negative floats order like their bit patterns), the block

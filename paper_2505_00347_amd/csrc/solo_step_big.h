@@ -165,7 +165,6 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     constexpr int CM = 32 / BM, CV = 32 / BV;
     constexpr int VT = K + 1;
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
-    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
     constexpr bool kDeTable = MDE && BM >= 3;
 
     const uint32_t tid = wave * 64u + lane;
@@ -226,85 +225,17 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
 
     // ---- coalesced layout -> 8 consecutive elements per lane
     float p[8], g[8];
-    {
-        float4 pa = raw.p0, pb = raw.p1;
-        uint4 ga = raw.g0, gb = raw.g1;
-        if (!TAIL) {
-            st_c[0] = pa; st_c[72] = pb;
-            wave_lds_sync();
-            pa = st_l[0]; pb = st_l[1];
-            if (!BF16) {
-                wave_lds_sync();
-                st_c[0] = make_float4(u2f(ga.x), u2f(ga.y), u2f(ga.z), u2f(ga.w));
-                st_c[72] = make_float4(u2f(gb.x), u2f(gb.y), u2f(gb.z), u2f(gb.w));
-                wave_lds_sync();
-                const float4 t0 = st_l[0], t1 = st_l[1];
-                ga = make_uint4(f2u(t0.x), f2u(t0.y), f2u(t0.z), f2u(t0.w));
-                gb = make_uint4(f2u(t1.x), f2u(t1.y), f2u(t1.z), f2u(t1.w));
-            }
-        }
-        p[0] = pa.x; p[1] = pa.y; p[2] = pa.z; p[3] = pa.w;
-        p[4] = pb.x; p[5] = pb.y; p[6] = pb.z; p[7] = pb.w;
-        if (BF16) {
-            g[0] = u2f(ga.x << 16); g[1] = u2f(ga.x & 0xFFFF0000u);
-            g[2] = u2f(ga.y << 16); g[3] = u2f(ga.y & 0xFFFF0000u);
-            g[4] = u2f(ga.z << 16); g[5] = u2f(ga.z & 0xFFFF0000u);
-            g[6] = u2f(ga.w << 16); g[7] = u2f(ga.w & 0xFFFF0000u);
-        } else {
-            g[0] = u2f(ga.x); g[1] = u2f(ga.y); g[2] = u2f(ga.z); g[3] = u2f(ga.w);
-            g[4] = u2f(gb.x); g[5] = u2f(gb.y); g[6] = u2f(gb.z); g[7] = u2f(gb.w);
-        }
-    }
+    lane_layout8<BF16, TAIL>(raw, st_c, st_l, p, g);
     if (EXT) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
     }
 
-    // ---- dequantize (table look-up), EMA, parameter
+    // ---- dequantize (table look-up), EMA, parameter; new parameters streamed out
     float mh[8], vh[8];
-    float m_absmax = 0.0f, v_max = 0.0f;
-    const float kb = a.belief ? 1.0f : 0.0f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t om = (j == 0) ? (mc8 << 2) : (mc8 >> (BM * j - 2));
-        const uint32_t ov = (j == 0) ? (vc8 << 2) : (vc8 >> (BV * j - 2));
-        const float mt = lds_f32(tm_addr | (om & MIDX));
-        const float vt = lds_f32(tv_addr | (ov & VIDX));
-        mh[j] = __builtin_fmaf(a.beta1, mt, a.omb1 * g[j]);
-        if (EXT) {
-            const float d = __builtin_fmaf(-kb, mh[j], g[j]);
-            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (d * d)) + a.eps_state;
-        } else {
-            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (g[j] * g[j]));
-        }
-        const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
-        p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
-        if (TAIL && !ok[j]) { mh[j] = 0.0f; vh[j] = 0.0f; }
-        m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
-        v_max = __builtin_fmaxf(v_max, vh[j]);
-    }
-    if (EXT && a.param_bf16) {
-        if (!TAIL) {
-            const u32x4_t h = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-            stream_store_u4(a.param_bf16 + e0, h);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (ok[j]) a.param_bf16[e0 + j] = (uint16_t)pack_bf16(p[j], 0.0f);
-        }
-    }
-    if (!TAIL) {
-        wave_lds_sync();
-        st_l[0] = make_float4(p[0], p[1], p[2], p[3]);
-        st_l[1] = make_float4(p[4], p[5], p[6], p[7]);
-        wave_lds_sync();
-        float *pp = a.param + ew0 + lane * 4u;
-        stream_store_f4(pp, st_c[0]);
-        stream_store_f4(pp + 256, st_c[72]);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) if (ok[j]) a.param[e0 + j] = p[j];
-    }
+    float m_absmax, v_max;
+    ema_param<8, BM, BV, EXT, TAIL, true>(a, tm_addr, tv_addr, &mc8, &vc8, ok, p, g, mh, vh, m_absmax, v_max);
+    store_params8<EXT, TAIL>(a, ew0, e0, lane, ok, p, st_c, st_l);
 
     // ---- the work area becomes the histograms of the selection: a wavefront clears its own staging
     // area (it is done with it; the others may still be using theirs) and its share of the rest
@@ -395,7 +326,7 @@ struct WideBigLayout {
     static constexpr int kSlab = 304;
 };
 static_assert(BigLayout::kWork >= kWideBigWaves * WideBigLayout::kStage, "the staging areas lie inside the work area");
-static_assert(288 * 4 <= WideBigLayout::kStage, "the padded transposition fits a staging area");
+static_assert(288 * 4 <= WideBigLayout::kStage, "the padded transposition (Stage16) fits a staging area");
 
 template <int BM, int BV, bool BF16, bool MDE, bool EXT>
 __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_t blk, const uint32_t lane,
@@ -407,7 +338,6 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
     constexpr int CM = 32 / BM, CV = 32 / BV;
     constexpr int VT = K + 1;
     constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
-    constexpr uint32_t MIDX = ((1u << BM) - 1u) << 2, VIDX = ((1u << BV) - 1u) << 2;
     constexpr bool kDeTable = MDE && BM >= 3;
     constexpr int KM = CM == 16 ? 1 : 2, KV = CV == 16 ? 1 : 2;      // words of a stream per lane (64 x K >= words of 1024 elements)
 
@@ -422,11 +352,7 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
     // ---- loads: parameters and gradients, the wavefront's code words, the block's scalars
     RawPG16<BF16> raw = load_pg16<BF16>(a, ew0, lane);
     const float gscale = (EXT && a.grad_scale) ? *a.grad_scale : 1.0f;
-    float4 *const stage = reinterpret_cast<float4 *>(work + wave * WideBigLayout::kStage);
-    float4 *const st4_c = stage + (lane + lane / 8u);       // + 72 k
-    float4 *const st4_l = stage + (4u * lane + lane / 2u);  // + c
-    float4 *const st2_c = stage + (lane + lane / 8u);       // + 72 k
-    float4 *const st2_l = stage + (2u * lane + lane / 4u);  // + c
+    const Stage16 st(reinterpret_cast<float4 *>(work + wave * WideBigLayout::kStage), lane);
     // words of the wavefront's 1024 elements: the first may start inside a word (ten-to-a-word
     // codes); all of them exist, the block is a full one
     const uint64_t gm_lo = ew0 / CM, gv_lo = ew0 / CV;
@@ -486,94 +412,17 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
 
     // ---- coalesced layout -> 16 consecutive elements per lane
     float p[16], g[16];
-    {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) st4_c[72 * k] = raw.p[k];
-        wave_lds_sync();
-        float4 t[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) t[c] = st4_l[c];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) { p[4 * c] = t[c].x; p[4 * c + 1] = t[c].y; p[4 * c + 2] = t[c].z; p[4 * c + 3] = t[c].w; }
-        wave_lds_sync();
-        if (BF16) {
-#pragma unroll
-            for (int k = 0; k < 2; ++k)
-                st2_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
-            wave_lds_sync();
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const float4 x = st2_l[c];
-                const uint32_t w[4] = {f2u(x.x), f2u(x.y), f2u(x.z), f2u(x.w)};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    g[8 * c + 2 * i] = u2f(w[i] << 16);
-                    g[8 * c + 2 * i + 1] = u2f(w[i] & 0xFFFF0000u);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < (BF16 ? 2 : 4); ++k)
-                st4_c[72 * k] = make_float4(u2f(raw.g[k].x), u2f(raw.g[k].y), u2f(raw.g[k].z), u2f(raw.g[k].w));
-            wave_lds_sync();
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const float4 x = st4_l[c];
-                g[4 * c] = x.x; g[4 * c + 1] = x.y; g[4 * c + 2] = x.z; g[4 * c + 3] = x.w;
-            }
-        }
-    }
+    lane_layout16<BF16>(raw, st, p, g);
     if (EXT) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) g[j] = __builtin_fmaf(a.l2, p[j], g[j] * gscale);
     }
 
-    // ---- dequantize (table look-up), EMA, parameter
+    // ---- dequantize (table look-up), EMA, parameter; new parameters streamed out
     float mh[16], vh[16];
-    float m_absmax = 0.0f, v_max = 0.0f;
-    const float kb = a.belief ? 1.0f : 0.0f;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int r = j / 8, jj = j % 8;
-        const uint32_t om = (jj == 0) ? (mc8[r] << 2) : (mc8[r] >> (BM * jj - 2));
-        const uint32_t ov = (jj == 0) ? (vc8[r] << 2) : (vc8[r] >> (BV * jj - 2));
-        const float mt = lds_f32(tm_addr | (om & MIDX));
-        const float vt = lds_f32(tv_addr | (ov & VIDX));
-        mh[j] = __builtin_fmaf(a.beta1, mt, a.omb1 * g[j]);
-        if (EXT) {
-            const float d = __builtin_fmaf(-kb, mh[j], g[j]);
-            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (d * d)) + a.eps_state;
-        } else {
-            vh[j] = __builtin_fmaf(a.beta2, vt, a.omb2 * (g[j] * g[j]));
-        }
-        const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vh[j]), a.denom_scale, a.denom_eps);
-        p[j] = __builtin_fmaf(p[j], a.decay, -(mh[j] * __builtin_amdgcn_rcpf(denom)));
-        m_absmax = __builtin_fmaxf(m_absmax, __builtin_fabsf(mh[j]));
-        v_max = __builtin_fmaxf(v_max, vh[j]);
-    }
-    // ---- new parameters back to the coalesced layout, streamed out
-    wave_lds_sync();
-    if (EXT && a.param_bf16) {
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const uint32_t h0 = pack_bf16(p[8 * c], p[8 * c + 1]), h1 = pack_bf16(p[8 * c + 2], p[8 * c + 3]);
-            const uint32_t h2 = pack_bf16(p[8 * c + 4], p[8 * c + 5]), h3 = pack_bf16(p[8 * c + 6], p[8 * c + 7]);
-            st2_l[c] = make_float4(u2f(h0), u2f(h1), u2f(h2), u2f(h3));
-        }
-        wave_lds_sync();
-        uint16_t *hp = a.param_bf16 + ew0 + lane * 8u;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) stream_store_f4(reinterpret_cast<float *>(hp + 512 * k), st2_c[72 * k]);
-        wave_lds_sync();
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) st4_l[c] = make_float4(p[4 * c], p[4 * c + 1], p[4 * c + 2], p[4 * c + 3]);
-    wave_lds_sync();
-    {
-        float *pp = a.param + ew0 + lane * 4u;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st4_c[72 * k]);
-    }
+    float m_absmax, v_max;
+    ema_param<16, BM, BV, EXT, false, true>(a, tm_addr, tv_addr, mc8, vc8, nullptr, p, g, mh, vh, m_absmax, v_max);
+    store_params16<EXT>(a, ew0, lane, p, st);
 
     // ---- the work area becomes the histograms of the selection: a wavefront clears its own staging
     // area (it is done with it; the other may still be using its own) and its share of the rest
