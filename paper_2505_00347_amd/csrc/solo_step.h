@@ -960,6 +960,37 @@ __device__ __forceinline__ void store_params8(const StepArgs &a, const uint64_t 
     }
 }
 
+// A lane's run of 8 new codes into the LDS image of the code words (wm / sm, wv / sv: word and
+// slot of the run's first code; xm, xv: old codes XOR new codes): the XOR turns this lane's old
+// fields into the new ones and leaves the neighbours' fields of a shared word alone.
+template <int BM, int BV>
+__device__ __forceinline__ void xor_into_image8(uint32_t *const img_m, uint32_t *const img_v, const uint32_t wm,
+                                                const uint32_t sm, const uint32_t wv, const uint32_t sv,
+                                                const uint32_t xm, const uint32_t xv)
+{
+    const uint32_t xm0 = (BM == 3) ? (xm << (3u * sm)) & 0x3FFFFFFFu : xm << (BM * sm);
+    const uint32_t xm1 = (BM == 3) ? (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30) : 0u;
+    const uint32_t xv0 = (BV == 3) ? (xv << (3u * sv)) & 0x3FFFFFFFu : xv << (BV * sv);
+    const uint32_t xv1 = (BV == 3) ? (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30) : 0u;
+    atomicXor(&img_m[wm], xm0);
+    if (BM == 3) atomicXor(&img_m[wm + 1], xm1);
+    atomicXor(&img_v[wv], xv0);
+    if (BV == 3) atomicXor(&img_v[wv + 1], xv1);
+}
+
+// A lane writes back the code word it staged (`own`: as it was loaded; `fin`: as it is in the
+// image now).  Two- and four-bit words are whole words of whole lines and are stored plainly.
+// Ten-to-a-word codes do not end on a line (or even on a word) at the end of a wavefront's share:
+// their words take this wavefront's changes by atomic XOR (the fields that two wavefronts own in
+// a shared word are disjoint), which is carried out at the memory side and leaves no partly
+// written line behind in the L2 of this die.
+template <int BITS>
+__device__ __forceinline__ void write_back_word(uint32_t *const word, const uint32_t fin, const uint32_t own)
+{
+    if (BITS != 3) *word = fin;
+    else if (fin != own) atomicXor(word, fin ^ own);
+}
+
 // One super-tile of TILE elements, processed by the calling wavefront: the whole step for the
 // elements [tile * TILE, (tile + 1) * TILE) of the buffers in `a` (TAIL: clipped to a.n, with
 // bounds checks on every element).  `slab` is this wavefront's LDS, `lds_de` the workgroup's DE
@@ -1179,17 +1210,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
         uint32_t m8, v8;
         encode_run<BM, BV, MDE, TAIL>(a, e0, mh, vh, ok, codec, de_base, m8, v8);
 
-        // ---- update the state image in place: XOR turns this lane's old fields into the new
-        // ones and leaves the neighbours' fields of a shared word alone
-        const uint32_t xm = mc8 ^ m8, xv = vc8 ^ v8;
-        const uint32_t xm0 = (BM == 3) ? (xm << (3u * sm)) & 0x3FFFFFFFu : xm << (BM * sm);
-        const uint32_t xm1 = (BM == 3) ? (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30) : 0u;
-        const uint32_t xv0 = (BV == 3) ? (xv << (3u * sv)) & 0x3FFFFFFFu : xv << (BV * sv);
-        const uint32_t xv1 = (BV == 3) ? (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30) : 0u;
-        atomicXor(&img_m[wm], xm0);
-        if (BM == 3) atomicXor(&img_m[wm + 1], xm1);
-        atomicXor(&img_v[wv], xv0);
-        if (BV == 3) atomicXor(&img_v[wv + 1], xv1);
+        xor_into_image8<BM, BV>(img_m, img_v, wm, sm, wv, sv, mc8 ^ m8, vc8 ^ v8);
         if (alone) {
             if (lig == 0 && blk_ok) {
                 const uint64_t gb = tile * NBT + bl;
@@ -1205,24 +1226,11 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     if (alone) {
-        // Every lane writes back the word it staged.  512 two- or four-bit codes are one or two
-        // whole 128-byte lines, stored plainly.  Ten-to-a-word codes do not end on a line (or even
-        // on a word) at the end of an iteration: their words take this wavefront's changes by
-        // atomic XOR (the fields of two neighbouring iterations in a shared word are disjoint),
-        // which is carried out at the memory side and leaves no partly written line behind in
-        // the L2 of this die.
+        // every lane writes back the word it staged
         const uint32_t w_m = wm_lo + lane, w_v = wv_lo + lane;
         const uint64_t gw_m = tile * MW + w_m, gw_v = tile * VW + w_v;
-        if (w_m <= wm_hi && (!TAIL || gw_m < m_total)) {
-            const uint32_t fin = img_m[w_m];
-            if (BM != 3) a.m_words[gw_m] = fin;
-            else if (fin != own_m) atomicXor(&a.m_words[gw_m], fin ^ own_m);
-        }
-        if (w_v <= wv_hi && (!TAIL || gw_v < v_total)) {
-            const uint32_t fin = img_v[w_v];
-            if (BV != 3) a.v_words[gw_v] = fin;
-            else if (fin != own_v) atomicXor(&a.v_words[gw_v], fin ^ own_v);
-        }
+        if (w_m <= wm_hi && (!TAIL || gw_m < m_total)) write_back_word<BM>(&a.m_words[gw_m], img_m[w_m], own_m);
+        if (w_v <= wv_hi && (!TAIL || gw_v < v_total)) write_back_word<BV>(&a.v_words[gw_v], img_v[w_v], own_v);
     } else {
         store_state_image<MW, VW, NBT>(a, tile, lane, img_m, img_v, sc);
     }
@@ -1352,6 +1360,47 @@ __device__ __forceinline__ void store_params16(const StepArgs &a, const uint64_t
     float *pp = a.param + chunk_e0 + lane * 4u;
 #pragma unroll
     for (int k = 0; k < 4; ++k) stream_store_f4(pp + 256 * k, st.c4[72 * k]);
+}
+
+// Codes of a lane's 16 elements (two runs of 8: e0 is the first element, wm / sm / wv / sv the
+// word and slot of each run's first code in the image, mc8 / vc8 the old codes) into the LDS
+// image of the code words.  3-bit codes share words between lanes: XOR turns this lane's old
+// fields into the new ones and leaves the neighbours' alone.  2- and 4-bit words belong to one lane
+// (2-bit: both runs lie in word wm[0]).
+template <int BM, int BV, bool MDE>
+__device__ __forceinline__ void encode_into_image16(const StepArgs &a, const uint64_t e0, const float *mh, const float *vh,
+                                                    const BlockCodec &codec, const uint32_t de_base,
+                                                    uint32_t *const img_m, uint32_t *const img_v,
+                                                    const uint32_t (&wm)[2], const uint32_t (&sm)[2],
+                                                    const uint32_t (&wv)[2], const uint32_t (&sv)[2],
+                                                    const uint32_t (&mc8)[2], const uint32_t (&vc8)[2])
+{
+    uint32_t m_word = 0, v_word = 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        uint32_t m8, v8;
+        encode_run<BM, BV, MDE, false>(a, e0 + 8u * r, mh + 8 * r, vh + 8 * r, nullptr, codec, de_base, m8, v8);
+        if (BM == 3) {
+            const uint32_t xm = mc8[r] ^ m8;
+            atomicXor(&img_m[wm[r]], (xm << (3u * sm[r])) & 0x3FFFFFFFu);
+            atomicXor(&img_m[wm[r] + 1], (uint32_t)(((uint64_t)xm << (3u * sm[r])) >> 30));
+        } else if (BM == 4) {
+            img_m[wm[r]] = m8;
+        } else {
+            m_word |= m8 << (16 * r);
+            if (r == 1) img_m[wm[0]] = m_word;
+        }
+        if (BV == 3) {
+            const uint32_t xv = vc8[r] ^ v8;
+            atomicXor(&img_v[wv[r]], (xv << (3u * sv[r])) & 0x3FFFFFFFu);
+            atomicXor(&img_v[wv[r] + 1], (uint32_t)(((uint64_t)xv << (3u * sv[r])) >> 30));
+        } else if (BV == 4) {
+            img_v[wv[r]] = v8;
+        } else {
+            v_word |= v8 << (16 * r);
+            if (r == 1) img_v[wv[0]] = v_word;
+        }
+    }
 }
 
 // The wide path: the same step as step_tile() for a full super-tile, with 16 consecutive
@@ -1504,34 +1553,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         const float alpha = codec.alpha;
 
         // ---- encode and update the state image, one run of 8 elements at a time
-        uint32_t m_word = 0, v_word = 0;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            uint32_t m8, v8;
-            encode_run<BM, BV, MDE, false>(a, e0 + 8u * r, mh + 8 * r, vh + 8 * r, nullptr, codec, de_base, m8, v8);
-            // 3-bit codes share words between lanes: XOR turns this lane's old fields into the new
-            // ones and leaves the neighbours' alone.  2- and 4-bit words belong to one lane.
-            if (BM == 3) {
-                const uint32_t xm = mc8[r] ^ m8;
-                atomicXor(&img_m[wm[r]], (xm << (3u * sm[r])) & 0x3FFFFFFFu);
-                atomicXor(&img_m[wm[r] + 1], (uint32_t)(((uint64_t)xm << (3u * sm[r])) >> 30));
-            } else if (BM == 4) {
-                img_m[wm[r]] = m8;
-            } else {
-                m_word |= m8 << (16 * r);
-                if (r == 1) img_m[wm[0]] = m_word;
-            }
-            if (BV == 3) {
-                const uint32_t xv = vc8[r] ^ v8;
-                atomicXor(&img_v[wv[r]], (xv << (3u * sv[r])) & 0x3FFFFFFFu);
-                atomicXor(&img_v[wv[r] + 1], (uint32_t)(((uint64_t)xv << (3u * sv[r])) >> 30));
-            } else if (BV == 4) {
-                img_v[wv[r]] = v8;
-            } else {
-                v_word |= v8 << (16 * r);
-                if (r == 1) img_v[wv[0]] = v_word;
-            }
-        }
+        encode_into_image16<BM, BV, MDE>(a, e0, mh, vh, codec, de_base, img_m, img_v, wm, sm, wv, sv, mc8, vc8);
         if (lig == 0) { sc[bl] = dm; sc[NBT + bl] = dv; sc[2 * NBT + bl] = alpha; }
     }
 

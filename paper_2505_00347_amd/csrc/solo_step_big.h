@@ -279,27 +279,11 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
     const BlockCodec codec = block_codec<BV, 16, L, MDE>(xp_bits, dm, dv, lane, lig, gshift);
     uint32_t m8, v8;
     encode_run<BM, BV, MDE, TAIL>(a, e0, mh, vh, ok, codec, de_base, m8, v8);
-    const uint32_t xm = mc8 ^ m8, xv = vc8 ^ v8;
-    const uint32_t xm0 = (BM == 3) ? (xm << (3u * sm)) & 0x3FFFFFFFu : xm << (BM * sm);
-    const uint32_t xm1 = (BM == 3) ? (uint32_t)(((uint64_t)xm << (3u * sm)) >> 30) : 0u;
-    const uint32_t xv0 = (BV == 3) ? (xv << (3u * sv)) & 0x3FFFFFFFu : xv << (BV * sv);
-    const uint32_t xv1 = (BV == 3) ? (uint32_t)(((uint64_t)xv << (3u * sv)) >> 30) : 0u;
-    atomicXor(&img_m[wm], xm0);
-    if (BM == 3) atomicXor(&img_m[wm + 1], xm1);
-    atomicXor(&img_v[wv], xv0);
-    if (BV == 3) atomicXor(&img_v[wv + 1], xv1);
+    xor_into_image8<BM, BV>(img_m, img_v, wm, sm, wv, sv, mc8 ^ m8, vc8 ^ v8);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (has_m) {
-        const uint32_t fin = img_m[lane];
-        if (BM != 3) a.m_words[gw_m] = fin;
-        else if (fin != own_m) atomicXor(&a.m_words[gw_m], fin ^ own_m);
-    }
-    if (has_v) {
-        const uint32_t fin = img_v[lane];
-        if (BV != 3) a.v_words[gw_v] = fin;
-        else if (fin != own_v) atomicXor(&a.v_words[gw_v], fin ^ own_v);
-    }
+    if (has_m) write_back_word<BM>(&a.m_words[gw_m], img_m[lane], own_m);
+    if (has_v) write_back_word<BV>(&a.v_words[gw_v], img_v[lane], own_v);
     if (tid == 0) { a.m_scale[blk] = dm; a.v_scale[blk] = dv; a.v_base[blk] = codec.alpha; }
 }
 
@@ -460,52 +444,15 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
     uint32_t de_base = 0;
     if (kDeTable) de_base = lds_addr(lds_de) - 16u * DeBuckets<BM>::kLo;
     const BlockCodec codec = block_codec<BV, 16, L, MDE>(xp_bits, dm, dv, lane, lig, gshift);
-    uint32_t m_word = 0, v_word = 0;
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        uint32_t m8, v8;
-        encode_run<BM, BV, MDE, false>(a, e0 + 8u * r, mh + 8 * r, vh + 8 * r, nullptr, codec, de_base, m8, v8);
-        // 3-bit codes share words between lanes: XOR turns this lane's old fields into the new
-        // ones and leaves the neighbours' alone.  2- and 4-bit words belong to one lane.
-        if (BM == 3) {
-            const uint32_t xm = mc8[r] ^ m8;
-            atomicXor(&img_m[wm[r]], (xm << (3u * sm[r])) & 0x3FFFFFFFu);
-            atomicXor(&img_m[wm[r] + 1], (uint32_t)(((uint64_t)xm << (3u * sm[r])) >> 30));
-        } else if (BM == 4) {
-            img_m[wm[r]] = m8;
-        } else {
-            m_word |= m8 << (16 * r);
-            if (r == 1) img_m[wm[0]] = m_word;
-        }
-        if (BV == 3) {
-            const uint32_t xv = vc8[r] ^ v8;
-            atomicXor(&img_v[wv[r]], (xv << (3u * sv[r])) & 0x3FFFFFFFu);
-            atomicXor(&img_v[wv[r] + 1], (uint32_t)(((uint64_t)xv << (3u * sv[r])) >> 30));
-        } else if (BV == 4) {
-            img_v[wv[r]] = v8;
-        } else {
-            v_word |= v8 << (16 * r);
-            if (r == 1) img_v[wv[0]] = v_word;
-        }
-    }
+    encode_into_image16<BM, BV, MDE>(a, e0, mh, vh, codec, de_base, img_m, img_v, wm, sm, wv, sv, mc8, vc8);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int k = 0; k < KM; ++k) {
-        if (lane + 64u * k < nwm) {
-            const uint32_t fin = img_m[lane + 64u * k];
-            if (BM != 3) a.m_words[gm_lo + lane + 64u * k] = fin;
-            else if (fin != own_m[k]) atomicXor(&a.m_words[gm_lo + lane + 64u * k], fin ^ own_m[k]);
-        }
-    }
+    for (int k = 0; k < KM; ++k)
+        if (lane + 64u * k < nwm) write_back_word<BM>(&a.m_words[gm_lo + lane + 64u * k], img_m[lane + 64u * k], own_m[k]);
 #pragma unroll
-    for (int k = 0; k < KV; ++k) {
-        if (lane + 64u * k < nwv) {
-            const uint32_t fin = img_v[lane + 64u * k];
-            if (BV != 3) a.v_words[gv_lo + lane + 64u * k] = fin;
-            else if (fin != own_v[k]) atomicXor(&a.v_words[gv_lo + lane + 64u * k], fin ^ own_v[k]);
-        }
-    }
+    for (int k = 0; k < KV; ++k)
+        if (lane + 64u * k < nwv) write_back_word<BV>(&a.v_words[gv_lo + lane + 64u * k], img_v[lane + 64u * k], own_v[k]);
     if (tid == 0) { a.m_scale[blk] = dm; a.v_scale[blk] = dv; a.v_base[blk] = codec.alpha; }
 }
 
