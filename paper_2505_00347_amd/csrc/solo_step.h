@@ -840,6 +840,33 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
 
 // ---- pieces shared by the tile functions and the large-block functions (solo_step_big.h)
 
+// The level tables of a block that G lanes share (decode by table look-up): lane `lig` of the group
+// fills entries lig, lig + G, ... of the 2nd-moment table (Delta_v alpha^q, alpha^q by binary
+// powering) and of the 1st-moment table (linear: (c - L) (Delta_m / L); dynamic exponent: the
+// lane's levels `de_level` times Delta_m).
+template <int BM, int BV, bool MDE, int G>
+__device__ __forceinline__ void fill_level_tables(float *const my_tv, float *const my_tm, const uint32_t lig,
+                                                  const float dm_old, const float dv_old, const float al_old,
+                                                  const float *de_level)
+{
+    constexpr int L = (1 << (BM - 1)) - 1;
+    constexpr int VT = 1 << BV;
+    constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
+    const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
+    const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
+#pragma unroll
+    for (int r = 0; r < (VT + G - 1) / G; ++r) {
+        const uint32_t q = lig + r * G;
+        if (q < VT) my_tv[q] = log_level<BV>(q, P1, P2, P4, P8) * dv_old;
+    }
+#pragma unroll
+    for (int r = 0; r < (MT + G - 1) / G; ++r) {
+        const uint32_t c = lig + r * G;
+        if (c < MT) my_tm[c] = MDE ? de_level[r] * dm_old : (float)((int)c - L) * s_m;
+    }
+}
+
+
 // A lane's 8 consecutive elements out of the coalesced layout they were loaded in, through the
 // wavefront's staging area: st_c = stage + lane + lane / 8 (coalesced slots st_c[0], st_c[72]),
 // st_l = stage + 2 lane + lane / 4 (the lane's own two vectors).  TAIL: loaded per lane already.
@@ -1133,18 +1160,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint64_t tile
 
         // ---- level tables of this lane's block: entries lig, lig + G, ...
         {
-            const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
-            const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
-#pragma unroll
-            for (int r = 0; r < (VT + G - 1) / G; ++r) {
-                const uint32_t q = lig + r * G;
-                if (q < VT) my_tv[q] = log_level<BV>(q, P1, P2, P4, P8) * dv_old;
-            }
-#pragma unroll
-            for (int r = 0; r < (MT + G - 1) / G; ++r) {
-                const uint32_t c = lig + r * G;
-                if (c < MT) my_tm[c] = MDE ? de_level[r] * dm_old : (float)((int)c - L) * s_m;
-            }
+            fill_level_tables<BM, BV, MDE, G>(my_tv, my_tm, lig, dm_old, dv_old, al_old, de_level);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
@@ -1497,20 +1513,7 @@ __device__ __forceinline__ void step_tile16(const StepArgs &a, const uint64_t ti
         }
 
         // ---- level tables of this lane's block: entries lig, lig + G
-        {
-            const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
-            const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
-#pragma unroll
-            for (int r = 0; r < (VT + G - 1) / G; ++r) {
-                const uint32_t q = lig + r * G;
-                if (q < VT) my_tv[q] = log_level<BV>(q, P1, P2, P4, P8) * dv_old;
-            }
-#pragma unroll
-            for (int r = 0; r < (MT + G - 1) / G; ++r) {
-                const uint32_t c = lig + r * G;
-                if (c < MT) my_tm[c] = MDE ? de_level[r] * dm_old : (float)((int)c - L) * s_m;
-            }
-        }
+        fill_level_tables<BM, BV, MDE, G>(my_tv, my_tm, lig, dm_old, dv_old, al_old, de_level);
 
         // ---- coalesced layout -> 16 consecutive elements per lane
         float p[16], g[16];

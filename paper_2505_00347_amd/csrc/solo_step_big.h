@@ -161,10 +161,7 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
                                                uint32_t *const xch, const uint32_t *const lds_de)
 {
     constexpr int L = (1 << (BM - 1)) - 1;
-    constexpr int K = (1 << BV) - 1;
     constexpr int CM = 32 / BM, CV = 32 / BV;
-    constexpr int VT = K + 1;
-    constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
     constexpr bool kDeTable = MDE && BM >= 3;
 
     const uint32_t tid = wave * 64u + lane;
@@ -201,10 +198,8 @@ __device__ __forceinline__ void step_block_big(const StepArgs &a, const uint64_t
 
     // ---- level tables of the block (every wavefront its own copy)
     {
-        const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
-        const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
-        if (lane < (uint32_t)VT) my_tv[lane] = log_level<BV>(lane, P1, P2, P4, P8) * dv_old;
-        if (lane < (uint32_t)MT) my_tm[lane] = MDE ? DeLevels<BM>::level(lane) * dm_old : (float)((int)lane - L) * s_m;
+        const float de_level = MDE ? DeLevels<BM>::level(lane) : 0.0f;
+        fill_level_tables<BM, BV, MDE, 64>(my_tv, my_tm, lane, dm_old, dv_old, al_old, &de_level);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -318,10 +313,7 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
                                                 uint32_t *const xch, const uint32_t *const lds_de)
 {
     constexpr int L = (1 << (BM - 1)) - 1;
-    constexpr int K = (1 << BV) - 1;
     constexpr int CM = 32 / BM, CV = 32 / BV;
-    constexpr int VT = K + 1;
-    constexpr int MT = MDE ? 2 * L + 2 : 2 * L + 1;
     constexpr bool kDeTable = MDE && BM >= 3;
     constexpr int KM = CM == 16 ? 1 : 2, KV = CV == 16 ? 1 : 2;      // words of a stream per lane (64 x K >= words of 1024 elements)
 
@@ -368,10 +360,8 @@ __device__ __forceinline__ void step_block_wide(const StepArgs &a, const uint64_
 
     // ---- level tables of the block (every wavefront its own copy)
     {
-        const float s_m = (L == 1) ? dm_old : dm_old / (float)L;
-        const float P1 = al_old, P2 = P1 * P1, P4 = P2 * P2, P8 = P4 * P4;
-        if (lane < (uint32_t)VT) my_tv[lane] = log_level<BV>(lane, P1, P2, P4, P8) * dv_old;
-        if (lane < (uint32_t)MT) my_tm[lane] = MDE ? DeLevels<BM>::level(lane) * dm_old : (float)((int)lane - L) * s_m;
+        const float de_level = MDE ? DeLevels<BM>::level(lane) : 0.0f;
+        fill_level_tables<BM, BV, MDE, 64>(my_tv, my_tm, lane, dm_old, dv_old, al_old, &de_level);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
