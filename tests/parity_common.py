@@ -47,7 +47,7 @@ _progress_started = []
 
 
 def progress(line):
-    """A line into gpurun_out/parity_progress.txt: long tests show that they are alive."""
+    """A line into parity_progress.txt of the run's output folder: long tests show that they are alive."""
     out = os.path.join(ROOT, "gpurun_out")
     os.makedirs(out, exist_ok=True)
     mode = "a" if _progress_started else "w"
