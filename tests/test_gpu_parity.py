@@ -511,6 +511,44 @@ def test_trained_state_with_clustered_second_moments(so, gpu, B, bm, bv):
     assert top > 2 * 2048 // (1 << bv), "the trained state is not clustered"
 
 
+@pytest.mark.parametrize("B,n,bm,bv", ((128, 70000, 2, 3), (64, 70000, 4, 4), (2048, 70000, 2, 3), (2048, 70000, 3, 3),
+                                       (128, (1 << 25) + 3 * TILE + 17, 2, 3)))
+def test_non_finite_gradients_stay_inside_their_blocks(so, gpu, B, n, bm, bv):
+    """A NaN or an infinity in the gradient spoils its own block and nothing else: the step
+    completes, and every block without such an entry equals the oracle's result for the same
+    gradients with the bad entries removed.
+    (The last case is large enough for the streaming kernels; the others run one wavefront per
+    512 elements, or one workgroup per block of 2048.)"""
+    import torch
+    from paper_2505_00347_amd import synth
+    oc, gc = make_cfgs(so, gpu, bm, bv, B, True)
+    p = synth.make_params(n)
+    st = so.State(n, oc)
+    side = GpuSide(gpu, n, gc)
+    rng = np.random.default_rng(B + bm)
+    g1, _ = grads_for("normal", n, 1e-3, 9100, True)
+    so.step_packed(p, g1, st, 1, oc, threads=8)            # a clean first step, so that the state is not the zero state
+    side.load(p, st)
+    g, _ = grads_for("normal", n, 1e-3, 9101, True)
+    bad = rng.choice(n, 24, replace=False)
+    dirty = g.copy()
+    dirty[bad[:8]] = np.nan
+    dirty[bad[8:16]] = np.inf
+    dirty[bad[16:]] = -np.inf
+    bits = (dirty.view(np.uint32) >> 16).astype(np.uint16)   # bf16 patterns of the (bf16-representable) values
+    side.step(dev(bits), 2)
+    torch.cuda.synchronize()
+    got = side.fetch()
+    p_before = p.astype(np.float64)
+    margin = so.step_packed(p, g, st, 2, oc, want_margin=True, threads=8)   # the oracle sees the clean gradients
+    spoiled = np.zeros(-(-n // B), bool)
+    spoiled[bad // B] = True
+    assert not np.isfinite(got[0][bad]).any()                # the parameters under the bad entries are lost
+    tainted = spoiled.copy()
+    flips = compare_step(so, oc, n, p, st, margin, got, 1e-6, 2e-6 * oc.lr, tainted, p_before=p_before)
+    assert flips <= flip_budget(n) and (tainted & ~spoiled).sum() <= flips
+
+
 # ------------------------------------------------------- many tensors in one launch
 
 @pytest.mark.parametrize("bm,bv,B,bf16,de,optimizer,extras", [(2, 3, 128, True, False, "adamw", False),
