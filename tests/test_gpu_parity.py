@@ -25,9 +25,13 @@ def gpu():
 class GpuSide:
     """Device copy of (param, state) plus the C-ABI calls."""
 
-    def __init__(self, solo, n, cfg, grad_scale=None, bf16_copy=False):
+    def __init__(self, solo, n, cfg, grad_scale=None, bf16_copy=False, multi=False):
         import torch
         self.solo, self.n, self.cfg = solo, n, cfg
+        # multi: the buffer goes through solo_adamw_step_multi as a table of one tensor, which runs
+        # the streaming kernels on its full units whatever the size (a flat buffer of a test's
+        # size runs one wavefront per 512 elements)
+        self.multi = multi
         self.state = solo.SoloState(n, cfg)
         self.p = None
         self.grad_scale = None if grad_scale is None else torch.tensor([grad_scale], dtype=torch.float32,
@@ -42,6 +46,10 @@ class GpuSide:
         s.m_scale.copy_(dev(st.m_scale)); s.v_scale.copy_(dev(st.v_scale)); s.v_base.copy_(dev(st.v_base))
 
     def step(self, g_dev, step):
+        if self.multi:
+            table = self.solo.SoloMultiTable([(self.p, g_dev, self.state, self.p_bf16)], self.cfg)
+            table.step(step, grad_scale=self.grad_scale)
+            return
         self.state.step(self.p, g_dev, step, param_bf16=self.p_bf16, grad_scale=self.grad_scale)
 
     def check_bf16_copy(self, so):
@@ -71,12 +79,12 @@ def grads_for(kind, n, std, seed, bf16):
 
 
 def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal", std=1e-3,
-                       seed0=100, bf16_copy=False, **kw):
+                       seed0=100, bf16_copy=False, multi=False, **kw):
     from paper_2505_00347_amd import synth
     oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
     p = synth.make_params(n)
     st = so.State(n, oc)
-    side = GpuSide(solo, n, gc, kw.get("grad_scale"), bf16_copy)
+    side = GpuSide(solo, n, gc, kw.get("grad_scale"), bf16_copy, multi)
     flips = 0
     for step in range(1, steps + 1):
         g, g_dev = grads_for(kind, n, std, seed0 + step, bf16)
@@ -91,12 +99,12 @@ def run_teacher_forced(so, solo, n, bm, bv, B, bf16=False, steps=3, kind="normal
 
 
 def run_free(so, solo, n, bm, bv, B, bf16=False, steps=10, kind="normal", std=1e-3, seed0=100,
-             bf16_copy=False, **kw):
+             bf16_copy=False, multi=False, **kw):
     from paper_2505_00347_amd import synth
     oc, gc = make_cfgs(so, solo, bm, bv, B, bf16, **kw)
     p = synth.make_params(n)
     st = so.State(n, oc)
-    side = GpuSide(solo, n, gc, kw.get("grad_scale"), bf16_copy)
+    side = GpuSide(solo, n, gc, kw.get("grad_scale"), bf16_copy, multi)
     side.p = dev(p)
     got = side.fetch()                       # solo_state_init against the oracle's zero state
     assert np.array_equal(got[1], st.m_words) and np.array_equal(got[3], st.v_words)
@@ -192,6 +200,23 @@ def test_all_formats(so, gpu, bm, bv):
         run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=7 * bm + bv)
 
 
+@pytest.mark.parametrize("bm", (2, 3, 4))
+@pytest.mark.parametrize("bv", (2, 3, 4))
+def test_streaming_kernels_all_formats(so, gpu, bm, bv):
+    """The kernels that own a whole super-tile per wavefront (8 or 16 elements per lane, chosen by
+    the format) serve flat buffers only from 2^25 elements on; through a table of one tensor they
+    run at any size.  Every format, both block sizes, both codebooks with bf16 gradients, the
+    dynamic-exponent codebook with fp32 gradients, plain and with every extra: several super-tiles
+    and a ragged end."""
+    n = 3 * TILE + 2 * 2560 + 1283
+    for B in (128, 64):
+        for de, bf16 in ((False, True), (True, True), (True, False)):
+            run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=300 + 10 * bm + bv + B, de=de, multi=True,
+                               kind="normal_outliers" if bf16 else "student_t3", std=1e-4 if bf16 else 1e-3)
+    run_teacher_forced(so, gpu, n, bm, bv, 128, bf16=True, steps=3, seed0=400 + 10 * bm + bv, multi=True,
+                       optimizer="adam_l2", grad_scale=0.25, bf16_copy=True, wd=0.1)
+
+
 WIDE_FORMATS = [(bm, bv, 128, de) for de in (False, True)
                 for bm, bv in ((2, 2), (2, 3), (2, 4), (3, 2), (3, 3), (4, 2))] + \
                [(bm, bv, 64, de) for de in (False, True) for bm, bv in ((2, 2), (2, 3), (3, 2))]
@@ -202,12 +227,16 @@ def test_wide_path_formats(so, gpu, bm, bv, B, de):
     """The formats whose full super-tiles run 16 elements per lane (8 lanes per 128-element
     block, 4 per 64-element block): both gradient types, the plain step and the one with every
     extra, four full tiles and a ragged end (which runs the 8-elements-per-lane code on the same
-    state)."""
+    state).  A flat buffer reaches these kernels only from 2^25 elements on, so the buffer goes in
+    as a table of one tensor, whose full units run them at any size (fp32 gradients with the linear
+    codebook have no such kernels in use: their flat and multi-tensor launches run one wavefront
+    per 512 elements, which the flat call here covers)."""
     n = 4 * TILE + 3000
     for bf16 in (True, False):
-        run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=900 + 10 * bm + bv, de=de,
+        multi = bf16 or de
+        run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, seed0=900 + 10 * bm + bv, de=de, multi=multi,
                            std=1e-4 if bf16 else 1e-3, kind="normal_outliers" if bf16 else "student_t3")
-        run_free(so, gpu, n, bm, bv, B, bf16=bf16, steps=5, seed0=950 + 10 * bm + bv, de=de,
+        run_free(so, gpu, n, bm, bv, B, bf16=bf16, steps=5, seed0=950 + 10 * bm + bv, de=de, multi=multi,
                  optimizer="adabelief", grad_scale=0.5, bf16_copy=True, eps=1e-12)
 
 
