@@ -292,6 +292,11 @@ def test_quantile_settings_and_nearest_rounding(so, gpu):
         run_teacher_forced(so, gpu, n, 2, 3, 64, steps=3, p=p, seed0=int(p * 100) + 1)
     run_teacher_forced(so, gpu, n, 3, 3, 128, steps=4, stochastic=0, seed0=77)
     run_free(so, gpu, n, 2, 4, 128, steps=6, stochastic=0, seed0=78)
+    # the same on the streaming kernels (a table of one tensor): 16 and 8 elements per lane
+    for p in (0.0, 0.05, 0.3, 0.5, 0.95):
+        run_teacher_forced(so, gpu, n, 2, 3, 128, bf16=True, steps=3, p=p, seed0=int(p * 100) + 2, multi=True, std=1e-4)
+        run_teacher_forced(so, gpu, n, 4, 4, 64, bf16=True, steps=3, p=p, seed0=int(p * 100) + 3, multi=True, de=True)
+    run_free(so, gpu, n, 3, 3, 128, bf16=True, steps=6, stochastic=0, seed0=79, multi=True)
 
 
 def test_index_offset_and_seed(so, gpu):
@@ -331,18 +336,24 @@ def test_nearly_constant_blocks(so, gpu, eps):
               off=265625140904, kind="student_t3", std=5.4e-5)
     run_teacher_forced(so, gpu, 13899, 2, 3, 128, bf16=True, steps=3, seed0=358133, **kw)
     run_teacher_forced(so, gpu, 3 * TILE + 100, 4, 4, 64, bf16=False, steps=2, seed0=11, **kw)
+    run_teacher_forced(so, gpu, 3 * TILE + 100, 2, 3, 128, bf16=True, steps=3, seed0=358134, multi=True, **kw)   # streaming kernels
+    run_teacher_forced(so, gpu, 3 * TILE + 100, 4, 4, 64, bf16=False, steps=2, seed0=12, multi=True, **kw)
 
 
 @pytest.mark.parametrize("bm,bv,B,bf16,de", [(2, 3, 128, False, False), (4, 4, 64, False, False),
                                               (3, 2, 128, True, False), (4, 2, 128, False, True),
                                               (2, 2, 64, True, True)])
-def test_degenerate_blocks(so, gpu, bm, bv, B, bf16, de):
+@pytest.mark.parametrize("multi", (False, True))
+def test_degenerate_blocks(so, gpu, bm, bv, B, bf16, de, multi):
+    """Constant, zero and sparse blocks, an all-zero step, rows that stay idle.  multi: as a table
+    of one tensor, two super-tiles longer, so that the streaming kernels (or, with fp32 gradients
+    and the linear codebook, the multi-tensor form of the one-wavefront-per-512 kernels) see them."""
     from paper_2505_00347_amd import synth
-    n = 24 * B + 11
+    n = 24 * B + 11 + (2 * TILE if multi else 0)
     oc, gc = make_cfgs(so, gpu, bm, bv, B, bf16, de=de)
     p = synth.make_params(n)
     st = so.State(n, oc)
-    side = GpuSide(gpu, n, gc)
+    side = GpuSide(gpu, n, gc, multi=multi)
     for step in range(1, 9):
         g = special_grads(n, B, step) if step != 5 else np.zeros(n, np.float32)   # one all-zero step
         if step in (6, 7):
@@ -690,10 +701,11 @@ def random_cases(so, gpu, seed, blocks, cases):
         if rng.integers(0, 2):
             kw.update(grad_scale=float(rng.choice([1.0, 0.5, 1.0 / 1024])), bf16_copy=True)
         try:
+            # every other case as a table of one tensor (the streaming kernels on its full units)
             run_teacher_forced(so, gpu, n, bm, bv, B, bf16=bf16, steps=3, kind=kind, std=std,
-                               seed0=int(rng.integers(0, 10 ** 6)), **kw)
+                               seed0=int(rng.integers(0, 10 ** 6)), multi=c % 2 == 1, **kw)
         except AssertionError as e:
-            raise AssertionError(f"case {c}: n={n} m{bm} v{bv} B{B} bf16={bf16} {kind} std={std:.3g} {kw}: {e}") from e
+            raise AssertionError(f"case {c}: n={n} m{bm} v{bv} B{B} bf16={bf16} {kind} std={std:.3g} table={c % 2 == 1} {kw}: {e}") from e
 
 
 @pytest.mark.parametrize("seed", (1, 2, 3))

@@ -405,12 +405,15 @@ def test_config5_full_size_every_tile_exactly_once(so, gpu, name):
 
 # ------------------------------------------------------- sparse embedding rows (Sec. 3.2.2)
 
-def test_config5_sparse_embedding_rows(so, gpu):
+@pytest.mark.parametrize("launch", ("flat", "table"))
+def test_config5_sparse_embedding_rows(so, gpu, launch):
     """2048 rows of the LLaMA embedding (4096 wide): every step, 90 % of the rows (drawn afresh)
     receive no gradient, the case Sec. 3.2.2 raises for the adaptive base: their v^ = beta2 v~
     sit on at most eight distinct values per block (every extraction round of the quantile is
     a tie), blocks go to and come from the zero state, x_p = 0 blocks clamp the base.  Ten
-    teacher-forced and ten free-running steps, every element."""
+    teacher-forced and ten free-running steps, every element.  The flat buffer (8.4 M elements)
+    runs one wavefront per 512 elements; as a table of one tensor it runs the streaming kernel
+    of the metric's format, 16 elements per lane."""
     from paper_2505_00347_amd import synth
     from test_gpu_parity import GpuSide
     solo = gpu
@@ -420,7 +423,8 @@ def test_config5_sparse_embedding_rows(so, gpu):
     oc, gc = workload_cfgs(so, solo, w)
     p = synth.make_params(n)
     st = so.State(n, oc)
-    tf, fr = GpuSide(solo, n, gc), GpuSide(solo, n, gc)
+    multi = launch == "table"
+    tf, fr = GpuSide(solo, n, gc, multi=multi), GpuSide(solo, n, gc, multi=multi)
     fr.p = dev(p)
     tainted = np.zeros(st.m_scale.size, bool)
     flips_tf = flips_fr = 0
@@ -440,7 +444,7 @@ def test_config5_sparse_embedding_rows(so, gpu):
         flips_tf += compare_step(so, oc, n, p, st, margin, tf.fetch(), 1e-6, 2e-6 * oc.lr, p_before=p_before)
         flips_fr += compare_step(so, oc, n, p, st, margin, fr.fetch(), 1e-5, 1e-5 * oc.lr, tainted)
     zero_blocks = int((st.v_scale == 0).sum())
-    note(f"c5 sparse embedding rows ({rows} x {row_len}, {idle_seen / (10 * rows):.0%} of the rows idle per step): "
+    note(f"c5 sparse embedding rows, {launch} ({rows} x {row_len}, {idle_seen / (10 * rows):.0%} of the rows idle per step): "
          f"teacher-forced {flips_tf} flips, free-running {flips_fr} flips, {int(tainted.sum())} blocks diverged; "
          f"{zero_blocks} of {st.v_scale.size} blocks still in the zero state after 10 steps")
     assert flips_tf <= flip_budget(10 * n) and flips_fr <= flip_budget(10 * n)
