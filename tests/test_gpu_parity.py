@@ -395,6 +395,32 @@ def test_empty_and_invalid_arguments(gpu):
         solo.solo_adamw_step(*args, 2560, 0, cfg)
 
 
+def test_state_region_allocates_and_returns_its_spacer(gpu):
+    """The placement helper of the binding: inside it the state is allocated behind a spacer that
+    fills the first 96 GiB of the process's allocations; the spacer goes back to the driver on
+    exit, the state stays usable."""
+    import torch
+    solo = gpu
+    cfg = solo.make_config(2, 3, 128, 1)
+    n = 1 << 20
+    p = torch.zeros(n, device="cuda")
+    g = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free0 = torch.cuda.mem_get_info()[0]
+    with solo.state_region(6 * n) as region:
+        had_spacer = region.spacer is not None
+        assert had_spacer == (free0 > solo.HBM_REGION_BYTES + (8 << 30))
+        if had_spacer:
+            assert torch.cuda.mem_get_info()[0] < free0 - (90 << 30)
+        st = solo.SoloState(n, cfg)
+    assert region.spacer is None
+    assert torch.cuda.mem_get_info()[0] > free0 - (1 << 30)          # only the state (and torch's block for it) is left
+    st.step(p, g, 1)
+    torch.cuda.synchronize()
+    assert bool((st.v_scale == 0).all())                             # zero gradients: the zero state stays
+
+
 def test_runs_on_the_callers_stream(so, gpu):
     import torch
     from paper_2505_00347_amd import synth
