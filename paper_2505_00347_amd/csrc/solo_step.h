@@ -775,7 +775,7 @@ __device__ __forceinline__ BlockCodec block_codec(uint32_t xp_bits, float dm, fl
 // xi: one hashed start and stride per 8 elements, every element's word finalized on its own;
 // 1.5 + xi - 2^-24 is built as a float in [1,2) by one bit-align of the finalized word.
 // Codes are rounded in the float domain, four to an
-// accumulator: m: code - L = rint(m^ * L/Delta_m) in [-L, L];
+// accumulator (element j weighs 2^(b (j mod 4))): m: code - L = rint(m^ * L/Delta_m) in [-L, L];
 // v: code + 1 = floor(log_alpha(v^/Delta_v) + 1.5 + xi).  `ok` (TAIL only): the elements that exist.
 template <int BM, int BV, bool MDE, bool TAIL>
 __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const float *mh, const float *vh,
@@ -789,11 +789,11 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
     uint32_t X = mix32(((uint32_t)gidx ^ a.key0) + (uint32_t)(gidx >> 32) * a.key2);
     uint32_t Y = mix32(X ^ a.key1) | 1u;
     if (!a.stochastic) { X = kXiZeroWord; Y = 0u; }     // xi = 0: the float is 1.5
-    uint32_t xj = X + ((Y << 3) - Y);                   // X + j Y, walked down from j = 7
+    uint32_t xj = X;                                    // X + j Y, walked up from j = 0
     float am_lo = 0.0f, am_hi = 0.0f, av_lo = 0.0f, av_hi = 0.0f;
     uint32_t m8_de = 0;
 #pragma unroll
-    for (int j = 7; j >= 0; --j, xj -= Y) {
+    for (int j = 0; j < 8; ++j, xj += Y) {
         float tm = 0.0f;
         if (!MDE) {
             tm = __builtin_rintf(mh[j] * c.inv_s);
@@ -827,10 +827,12 @@ __device__ __forceinline__ void encode_run(const StepArgs &a, uint64_t e, const 
         float tv = __builtin_floorf(__builtin_fmaf(__builtin_amdgcn_logf(ratio), c.inv_l2a, f));
         tv = __builtin_amdgcn_fmed3f(tv, 1.0f, (float)(K + 1));   // +inf (v^ = 0) takes the last code
         if (TAIL && !ok[j]) { tm = -(float)L; tv = 1.0f; }
-        if (j == 7)      { am_hi = tm; av_hi = tv; }
-        else if (j >= 4) { am_hi = __builtin_fmaf(am_hi, (float)(1 << BM), tm); av_hi = __builtin_fmaf(av_hi, (float)(1 << BV), tv); }
-        else if (j == 3) { am_lo = tm; av_lo = tv; }
-        else             { am_lo = __builtin_fmaf(am_lo, (float)(1 << BM), tm); av_lo = __builtin_fmaf(av_lo, (float)(1 << BV), tv); }
+        // (sums of at most four small integers times powers of two: exact)
+        const float wm = (float)(1 << (BM * (j & 3))), wv = (float)(1 << (BV * (j & 3)));
+        if (j == 0)      { am_lo = tm; av_lo = tv; }
+        else if (j < 4)  { am_lo = __builtin_fmaf(tm, wm, am_lo); av_lo = __builtin_fmaf(tv, wv, av_lo); }
+        else if (j == 4) { am_hi = tm; av_hi = tv; }
+        else             { am_hi = __builtin_fmaf(tm, wm, am_hi); av_hi = __builtin_fmaf(tv, wv, av_hi); }
     }
     constexpr float OFFM = (float)(L * ((1 << (4 * BM)) - 1) / ((1 << BM) - 1));   // L * sum 2^(BM j), j < 4
     constexpr float OFFV = (float)(((1 << (4 * BV)) - 1) / ((1 << BV) - 1));        // sum 2^(BV j), j < 4
