@@ -542,8 +542,9 @@ def test_block_2048_config5_shape_ten_steps(so, gpu):
     note(f"block 2048, config-5 format, 2.1 M elements x 10 free-running steps: {flips} flips, {tainted} blocks diverged")
 
 
-@pytest.mark.parametrize("B,bm,bv", ((2048, 2, 3), (2048, 4, 2), (128, 2, 3)))
-def test_trained_state_with_clustered_second_moments(so, gpu, B, bm, bv):
+@pytest.mark.parametrize("B,bm,bv,multi", ((2048, 2, 3, False), (2048, 4, 2, False), (128, 2, 3, False),
+                                             (128, 2, 3, True), (2048, 2, 3, True)))
+def test_trained_state_with_clustered_second_moments(so, gpu, B, bm, bv, multi):
     """After some hundred updates the second moments of a block sit in a few tight clusters (beta2
     times one of the 2^b decoded levels, plus a small fresh term): most keys of the quantile
     selection then share their leading bits, the case the histograms of the large-block kernels
@@ -554,7 +555,7 @@ def test_trained_state_with_clustered_second_moments(so, gpu, B, bm, bv):
     from parity_common import DeviceView
     n = 40 * 2048 + 1283
     oc, gc = make_cfgs(so, gpu, bm, bv, B, True)
-    side = GpuSide(gpu, n, gc)
+    side = GpuSide(gpu, n, gc, multi=multi)              # multi: a table of one tensor (the streaming kernels for B = 128)
     side.p = dev(synth.make_params(n))
     grads = [grads_for("normal_outliers", n, 1e-4, 5000 + k, True) for k in range(8)]
     for step in range(1, 301):
