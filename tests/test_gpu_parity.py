@@ -302,6 +302,11 @@ def test_quantile_settings_and_nearest_rounding(so, gpu):
 def test_index_offset_and_seed(so, gpu):
     run_teacher_forced(so, gpu, 6000, 2, 3, 128, steps=3, off=8 * (1 << 33) + 2560 * 7, seed=123456789)
     run_teacher_forced(so, gpu, 6000, 4, 4, 64, steps=3, off=8, seed=0)
+    # the streaming kernels (a table of one tensor), with an offset whose group index crosses 2^32 inside the buffer
+    run_teacher_forced(so, gpu, 3 * TILE + 100, 2, 3, 128, bf16=True, steps=3, off=8 * ((1 << 32) - 700), seed=987654321,
+                       multi=True, std=1e-4)
+    run_teacher_forced(so, gpu, 3 * TILE + 100, 2, 3, 2048, bf16=True, steps=3, off=8 * ((1 << 32) - 700), seed=5,
+                       std=1e-4)
 
 
 def test_hyperparameter_ranges(so, gpu):
@@ -309,6 +314,9 @@ def test_hyperparameter_ranges(so, gpu):
     run_teacher_forced(so, gpu, 5000, 2, 2, 128, steps=3, beta1=0.1, beta2=0.98, lr=3e-4, wd=0.1)
     run_teacher_forced(so, gpu, 5000, 3, 3, 64, steps=3, std=30.0)            # large gradients
     run_teacher_forced(so, gpu, 5000, 3, 3, 64, steps=3, std=1e-9, bf16=True)  # tiny gradients
+    for kw in (dict(beta1=0.0, beta2=0.0, lr=1e-2, wd=0.0, eps=1e-6), dict(beta1=0.1, beta2=0.98, lr=3e-4, wd=0.1),
+               dict(std=30.0), dict(std=1e-9)):                                # the same on the streaming kernels
+        run_teacher_forced(so, gpu, 2 * TILE + 5000, 2, 3, 128, bf16=True, steps=3, multi=True, **kw)
 
 
 # ------------------------------------------------------------ degenerate inputs
