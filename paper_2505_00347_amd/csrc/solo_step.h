@@ -17,7 +17,14 @@
 // formats whose state image is small enough take step_tile16() instead: 16
 // elements per lane, 8 (4) lanes per block, 1024 elements per iteration, four
 // wavefronts per SIMD instead of five (fewer instructions per element; see
-// there).
+// there).  A ragged end, a short or mid-size buffer (chunked_up_to()) and the
+// formats whose streaming code sits at the register limit run step_tile() in
+// its `alone` form: one wavefront per 512-element iteration, which stages and
+// writes back only its own words (multi_chunk_kernel: the same over a table).
+// The pieces that these functions and the large-block functions of
+// solo_step_big.h have in common (layout transposition, level tables, EMAs
+// and parameter, encoders, image update, write-back) exist once, as inlined
+// helpers in front of step_tile().
 //
 // The kernel is bound by vector-ALU issue as much as by HBM (packed FP32 is
 // off, so a CU retires 64 lane-operations per clock: about 80 per parameter at
@@ -36,8 +43,10 @@
 //   * the base alpha = rho^(1/K) is found by testing G consecutive binary32
 //     candidates around a hardware exp2/log2 guess, one per lane;
 //   * codes are rounded in the float domain and accumulated with FMAs
-//     (acc = acc * 2^b + code); xi is built as a float in [1, 2) by one
-//     bit-align of the element's hashed word.
+//     (acc += code * 2^(b j)); xi is built as a float in [1, 2) by one
+//     bit-align of the element's finalized word of the xi stream (one hash
+//     per 8 elements gives a start and a stride, every word is then mixed
+//     on its own).
 //
 // Arithmetic contract (what makes the stored bytes reproducible): every value
 // that decides a code or a scale is computed in binary32, one rounding per
