@@ -15,6 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libsolo.so")
 PROBE = os.path.join(LIBDIR, "stream_probe")
+EXAMPLE = os.path.join(LIBDIR, "solo_c_example")
 SOURCES = ["solo_api.hip", "solo_step_m2.hip", "solo_step_m3.hip", "solo_step_m4.hip",
            "solo_step_m2_de.hip", "solo_step_m3_de.hip", "solo_step_m4_de.hip",
            "solo_step_big.hip", "solo_step_big_de.hip"]
@@ -49,6 +50,11 @@ def build(force=True, verbose=False):
                            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                            "-Wno-unknown-warning-option",
                            os.path.join(CSRC, "stream_probe.hip"), "-o", PROBE])
+    # a caller of the library without PyTorch (plain HIP memory and the C-ABI)
+    subprocess.check_call([HIPCC, "-O2", "--offload-arch=gfx950", "-std=c++17",
+                           "-Wno-unknown-warning-option", "-Wno-unused-result",
+                           os.path.join(CSRC, "solo_c_example.cpp"), "-o", EXAMPLE,
+                           "-L" + LIBDIR, "-lsolo", "-Wl,-rpath,$ORIGIN"])
     if verbose:
         print("built", LIB)
     return LIB
