@@ -96,7 +96,7 @@ def device_params(torch, w, seed):
     return p
 
 
-def cpu_baseline(w, sample, steps=3):
+def cpu_baseline(w, sample, steps=5):
     """The CPU oracle, as it stands, on the first `sample` elements of the workload's first
     tensor: with all host threads (median of the timed steps), and with one thread on an eighth
     of that sample."""
